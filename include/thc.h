@@ -1,0 +1,133 @@
+/*
+ * libthc -- Tensor Homomorphic Compression (arXiv 2302.08545), data-parallel hot path for AMD gfx950.
+ *
+ * One round of the paper's Alg. 3 ("Training with THC") for n workers whose buffers all live on one
+ * GPU maps onto four calls:
+ *
+ *   thc_prepare_range   preliminary stage: x_i = grad_i + e_i, per-block norms, the first half of the
+ *                       randomized Hadamard transform (the paper runs the norm exchange and the RHT in
+ *                       parallel), then the shared range M_k = t_p * max_i ||x_i|| / sqrt(B), m_k = -M_k
+ *   thc_compress        main stage, worker side: finish RHT, clamp to [-M, M], stochastic quantization
+ *                       onto the table's grid, table index, bit-pack; optional error-feedback update
+ *   thc_aggregate       main stage, parameter-server side: Y = sum_i T[Z_i] on the packed streams
+ *   thc_decompress      worker side: m + (Y/n)(M-m)/g, then the inverse RHT
+ *
+ * Conventions
+ *   - All data pointers are DEVICE pointers (hipMalloc'd, 16-byte aligned) unless a comment says "host".
+ *     Arrays of pointers (`grads`, `ef`, `packed`) are HOST arrays of device pointers.
+ *   - `stream` is a hipStream_t passed as void*.  Every call validates its arguments on the host,
+ *     enqueues its kernels on `stream` and returns without synchronizing.  Calls that share a workspace
+ *     must be ordered on one stream (or by events).
+ *   - The library allocates nothing and keeps no state: workspace, range, error-feedback buffers, the
+ *     round counter and the lookup table are owned by the caller.  Inputs are never modified, except
+ *     `ef_inout`.
+ *   - Return value: THC_OK (0) or a negative thc_status.  Non-finite inputs are not detected; they
+ *     propagate to unspecified (but in-bounds) results.
+ *   - Vector layout: a worker's gradient is one flat vector of d coordinates (padded by the caller with
+ *     zeros to a multiple of `block`).  The RHT, the norm and the range are per block of `block`
+ *     consecutive coordinates (the paper's 4 MB partition is block = 2^20).
+ *   - Packed index stream: coordinate j occupies bits [(j*b) mod 8, +b) of byte (j*b) div 8.
+ *   - Aggregated stream: one little-endian unsigned integer of agg_bits per coordinate.
+ *   - Random numbers: Philox4x32-10 keyed by `seed`.  Rademacher diagonal D^r: coordinate j takes bit
+ *     (j mod 32) of word ((j div 32) mod 4) of Philox(counter (q, q>>32, round, 0x80000000)), q = j div 128.
+ *     Rounding draw of worker i: coordinate j takes 16-bit half (j mod 8) (low half first) of
+ *     Philox(counter (q, q>>32, round, i)), q = j div 8; u = (half + 1/2) / 2^16.
+ *   - Butterflies of the Hadamard transform run in ascending stride order in binary32 without fused
+ *     multiply-add; packed bytes and aggregated sums are therefore reproducible bit for bit.
+ */
+#ifndef THC_H_
+#define THC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum thc_status {
+  THC_OK = 0,
+  THC_EINVAL = -1,       /* null or misaligned pointer, d/block/n/b/g out of range                         */
+  THC_ETABLE = -2,       /* table is not 0 = T[0] < T[1] < ... < T[2^b-1] = g (homomorphism precondition)   */
+  THC_EOVERFLOW = -3,    /* g*n does not fit in agg_bits                                                    */
+  THC_EUNSUPPORTED = -4, /* valid in principle, not implemented (e.g. n > THC_MAX_WORKERS)                  */
+  THC_ELAUNCH = -5       /* the HIP runtime rejected a launch; see hipGetLastError                          */
+} thc_status;
+
+enum { THC_MAX_WORKERS = 64 };
+enum { THC_DTYPE_F32 = 0, THC_DTYPE_BF16 = 1 };
+
+/* The problem statement of Alg. 3.  Plain data, owned by the caller, read on the host only. */
+typedef struct thc_params {
+  uint64_t d;          /* padded coordinate count per worker; a multiple of `block`                        */
+  uint64_t block;      /* B: RHT block, a power of two, 2^10 <= B <= 2^27, B divides d                     */
+  uint32_t n;          /* number of workers, 1 <= n <= THC_MAX_WORKERS                                     */
+  uint32_t b;          /* bits per table index: 1, 2, 4 or 8                                               */
+  uint32_t g;          /* granularity: 2^b - 1 <= g <= 255 (Sec. 4.3)                                      */
+  uint32_t agg_bits;   /* width of an aggregated value: 8 or 16; g*n < 2^agg_bits                          */
+  uint32_t in_dtype;   /* THC_DTYPE_F32 or THC_DTYPE_BF16 (widened to binary32 inside the kernel)          */
+  float    t_p;        /* truncation threshold Phi^-1(1 - p/2) (Sec. 5.1); see thc_threshold               */
+  uint64_t seed;       /* shared by all workers and the decompressor                                       */
+  uint8_t  table[256]; /* T[0 .. 2^b-1]; see thc_solve_table                                               */
+} thc_params;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int thc_version(void);
+
+/* Human-readable name of a status code (static storage). */
+const char* thc_strerror(int status);
+
+/* Bytes of device workspace the four calls below need for these parameters (host call, no GPU work).
+ * The workspace holds the half-rotated vectors of all n workers between thc_prepare_range and
+ * thc_compress (n*d binary32 values) plus the partial sums of squares. */
+int thc_workspace_bytes(const thc_params* p, size_t* bytes_out /* host */);
+
+/* Preliminary stage (Alg. 3: x_i = grad_i + e_i; send ||x_i||, receive the maximum -- in parallel with
+ * R_i = RHT(x_i); then M = (t_p / sqrt(d)) * l, m = -M; Sec. 5.3).
+ *   round     r of Alg. 3; selects the diagonal D^r.  Must be < 2^32.
+ *   grads     host array of n device pointers, each d values of in_dtype.
+ *   ef        host array of n device pointers to binary32 error-feedback buffers (read only here),
+ *             or NULL when error feedback is off.
+ *   range_M   device, d/block floats, written: M_k per block (m_k = -M_k).  May be NULL: then only the
+ *             half-rotated vectors are produced and the caller supplies its own range to thc_compress.
+ *   ws        device workspace of thc_workspace_bytes bytes, written. */
+int thc_prepare_range(const thc_params* p, uint64_t round, const void* const* grads /* host */,
+                      const float* const* ef /* host or NULL */, float* range_M, void* ws, void* stream);
+
+/* Main stage, worker side (Alg. 3: clamp, Q, SQ, Y_i, Z_i = T^-1[Y_i]; Alg. 2 worker steps; Sec. 4.1).
+ * Consumes the half-rotated vector that thc_prepare_range left in `ws` for this worker in this round.
+ *   worker_id   < n; selects the rounding stream.
+ *   grad        device, the same gradient given to thc_prepare_range (read only when ef_inout != NULL).
+ *   ef_inout    device binary32[d] or NULL.  When given: e <- (grad + e) - RHT^-1(X_i) with X_i the
+ *               dequantized vector (Alg. 3, error-feedback update).
+ *   range_M     device, d/block floats (from thc_prepare_range or from the caller).
+ *   packed_out  device, d*b/8 bytes, written. */
+int thc_compress(const thc_params* p, uint32_t worker_id, uint64_t round, const void* grad,
+                 float* ef_inout, const float* range_M, uint8_t* packed_out, void* ws, void* stream);
+
+/* Main stage, PS side (Alg. 2: Y = sum_i T[Z_i]; the PS pseudocode's lookup + aggregate steps).
+ *   packed    host array of n device pointers, each d*b/8 bytes.
+ *   agg_out   device, d * agg_bits/8 bytes, written.
+ * Aggregating a subset of workers (partial aggregation, Sec. 6) is a call with a smaller p->n. */
+int thc_aggregate(const thc_params* p, const uint8_t* const* packed /* host */, void* agg_out, void* stream);
+
+/* Worker side after the PS (Alg. 2 / Alg. 3: Y_avg = Y/n; x' = m + Y_avg (M-m)/g; RHT^-1).
+ *   agg   device, d * agg_bits/8 bytes.   out   device, d floats, written.   ws   device workspace. */
+int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const float* range_M,
+                   float* out, void* ws, void* stream);
+
+/* ---- host-side helpers (no GPU work) ------------------------------------------------------------- */
+
+/* t_p = Phi^-1(1 - p/2) (Sec. 5.1), 0 < p < 1. */
+double thc_threshold(double p);
+
+/* Optimal lookup table T_{b,g,p} of Sec. 5.2 / App. B: minimises the expected squared error of
+ * stochastic quantization of a standard normal truncated to [-t_p, t_p] over tables on the (g+1)-point
+ * grid.  Ties are broken towards the lexicographically smallest table.  Writes 2^b entries to
+ * table_out (host) and the attained cost (in units of sigma^2) to cost_out if not NULL. */
+int thc_solve_table(uint32_t b, uint32_t g, double p, uint8_t* table_out /* host */, double* cost_out /* host */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* THC_H_ */

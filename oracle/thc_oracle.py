@@ -415,7 +415,7 @@ def nmse(x: np.ndarray, xhat: np.ndarray) -> float:
 def t_p_of(p: float) -> float:
     """t_p = Phi^-1(1 - p/2)."""
     from scipy.special import ndtri
-    return float(ndtri(1.0 - p / 2.0))
+    return float(-ndtri(p / 2.0))       # = Phi^-1(1 - p/2) by symmetry, without the cancellation in 1 - p/2
 
 
 def _phi(a):

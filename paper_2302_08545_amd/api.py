@@ -1,0 +1,134 @@
+"""ctypes binding of libthc (include/thc.h).  Argument marshalling only: every step of the path runs
+in the HIP kernels.  PyTorch supplies device memory (`tensor.data_ptr()`) and the current stream."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_LIB = None
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libthc.so")
+
+THC_MAX_WORKERS = 64
+THC_DTYPE_F32, THC_DTYPE_BF16 = 0, 1
+
+EXPORTS = ("thc_version", "thc_strerror", "thc_workspace_bytes", "thc_prepare_range", "thc_compress",
+           "thc_aggregate", "thc_decompress", "thc_threshold", "thc_solve_table")
+
+
+class thc_params(C.Structure):
+    _fields_ = [("d", C.c_uint64), ("block", C.c_uint64), ("n", C.c_uint32), ("b", C.c_uint32),
+                ("g", C.c_uint32), ("agg_bits", C.c_uint32), ("in_dtype", C.c_uint32), ("t_p", C.c_float),
+                ("seed", C.c_uint64), ("table", C.c_uint8 * 256)]
+
+
+class ThcError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {thc_strerror(status)} ({status})")
+
+
+def lib():
+    """The loaded library.  Raises if it has not been built: there is no fallback path."""
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2302_08545_amd.build` "
+                               "(or __graft_entry__.build()) first")
+        L = C.CDLL(LIB_PATH)
+        vp, u64, u32 = C.c_void_p, C.c_uint64, C.c_uint32
+        pp = C.POINTER(thc_params)
+        L.thc_version.restype = C.c_int
+        L.thc_strerror.restype = C.c_char_p
+        L.thc_strerror.argtypes = [C.c_int]
+        L.thc_workspace_bytes.argtypes = [pp, C.POINTER(C.c_size_t)]
+        L.thc_prepare_range.argtypes = [pp, u64, C.POINTER(vp), C.POINTER(vp), vp, vp, vp]
+        L.thc_compress.argtypes = [pp, u32, u64, vp, vp, vp, vp, vp, vp]
+        L.thc_aggregate.argtypes = [pp, C.POINTER(vp), vp, vp]
+        L.thc_decompress.argtypes = [pp, u64, vp, vp, vp, vp, vp]
+        L.thc_threshold.restype = C.c_double
+        L.thc_threshold.argtypes = [C.c_double]
+        L.thc_solve_table.argtypes = [u32, u32, C.c_double, C.POINTER(C.c_uint8), C.POINTER(C.c_double)]
+        _LIB = L
+    return _LIB
+
+
+def make_params(d: int, block: int, n: int, b: int, g: int, t_p: float, seed: int, table: Sequence[int],
+                agg_bits: int = 8, in_dtype: int = THC_DTYPE_F32) -> thc_params:
+    p = thc_params()
+    p.d, p.block, p.n, p.b, p.g = d, block, n, b, g
+    p.agg_bits, p.in_dtype, p.t_p, p.seed = agg_bits, in_dtype, t_p, seed
+    for i, v in enumerate(table):
+        p.table[i] = int(v)
+    return p
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else (t if isinstance(t, int) else t.data_ptr())
+
+
+def _ptr_array(ts):
+    if ts is None:
+        return None
+    arr = (C.c_void_p * len(ts))()
+    for i, t in enumerate(ts):
+        arr[i] = _ptr(t)
+    return arr
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise ThcError(rc, where)
+
+
+def thc_version() -> int:
+    return lib().thc_version()
+
+
+def thc_strerror(status: int) -> str:
+    return lib().thc_strerror(status).decode()
+
+
+def thc_workspace_bytes(p: thc_params) -> int:
+    out = C.c_size_t(0)
+    _check(lib().thc_workspace_bytes(C.byref(p), C.byref(out)), "thc_workspace_bytes")
+    return out.value
+
+
+def thc_prepare_range(p: thc_params, rnd: int, grads, ef, range_M, ws, stream=None) -> None:
+    _check(lib().thc_prepare_range(C.byref(p), rnd, _ptr_array(grads), _ptr_array(ef), _ptr(range_M), _ptr(ws),
+                                   _stream(stream)), "thc_prepare_range")
+
+
+def thc_compress(p: thc_params, worker_id: int, rnd: int, grad, ef_inout, range_M, packed_out, ws,
+                 stream=None) -> None:
+    _check(lib().thc_compress(C.byref(p), worker_id, rnd, _ptr(grad), _ptr(ef_inout), _ptr(range_M),
+                              _ptr(packed_out), _ptr(ws), _stream(stream)), "thc_compress")
+
+
+def thc_aggregate(p: thc_params, packed, agg_out, stream=None) -> None:
+    _check(lib().thc_aggregate(C.byref(p), _ptr_array(packed), _ptr(agg_out), _stream(stream)), "thc_aggregate")
+
+
+def thc_decompress(p: thc_params, rnd: int, agg, range_M, out, ws, stream=None) -> None:
+    _check(lib().thc_decompress(C.byref(p), rnd, _ptr(agg), _ptr(range_M), _ptr(out), _ptr(ws), _stream(stream)),
+           "thc_decompress")
+
+
+def thc_threshold(p: float) -> float:
+    return lib().thc_threshold(p)
+
+
+def thc_solve_table(b: int, g: int, p: float):
+    """Returns (table as a list of 2^b ints, cost in sigma^2 units)."""
+    out = (C.c_uint8 * 256)()
+    cost = C.c_double(0.0)
+    _check(lib().thc_solve_table(b, g, p, out, C.byref(cost)), "thc_solve_table")
+    return [int(out[i]) for i in range(2 ** b)], cost.value

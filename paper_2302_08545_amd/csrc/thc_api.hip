@@ -1,0 +1,385 @@
+// C-ABI of libthc (see include/thc.h): host-side validation and kernel dispatch.
+#include "thc.h"
+
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "thc_kernels.hpp"
+
+namespace {
+
+using namespace thc;
+
+int ilog2(uint64_t v) {
+  int l = 0;
+  while ((1ull << l) < v) ++l;
+  return l;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int validate(const thc_params* p) {
+  if (!p) return THC_EINVAL;
+  if (p->block < (1ull << 10) || p->block > (1ull << 27) || (p->block & (p->block - 1))) return THC_EINVAL;
+  if (p->d == 0 || p->d % p->block) return THC_EINVAL;
+  if (p->n < 1) return THC_EINVAL;
+  if (p->n > THC_MAX_WORKERS) return THC_EUNSUPPORTED;
+  if (p->b != 1 && p->b != 2 && p->b != 4 && p->b != 8) return THC_EINVAL;
+  if (p->g < (1u << p->b) - 1 || p->g > 255) return THC_EINVAL;
+  if (p->agg_bits != 8 && p->agg_bits != 16) return THC_EINVAL;
+  if (p->in_dtype != THC_DTYPE_F32 && p->in_dtype != THC_DTYPE_BF16) return THC_EINVAL;
+  if (!(p->t_p > 0.f) || !std::isfinite(p->t_p)) return THC_EINVAL;
+  const uint32_t top = (1u << p->b) - 1;
+  if (p->table[0] != 0 || p->table[top] != p->g) return THC_ETABLE;
+  for (uint32_t z = 0; z < top; ++z)
+    if (p->table[z] >= p->table[z + 1]) return THC_ETABLE;
+  if ((uint64_t)p->g * p->n >= (1ull << p->agg_bits)) return THC_EOVERFLOW;
+  return THC_OK;
+}
+
+// Split of the log2(B) butterfly stages over the passes.
+struct Plan {
+  int L, L1;        // lo pass does bits [0, L1)
+  int mid[3];       // bit counts of the in-place middle passes
+  int nmid;
+  int R;            // hi pass does the top R bits
+  int s0_hi;        // log2 row pitch of the hi pass (>= 13 - R)
+};
+
+Plan make_plan(uint64_t block) {
+  Plan pl{};
+  pl.L = ilog2(block);
+  pl.L1 = pl.L < LOG_TILE ? pl.L : LOG_TILE;
+  int rem = pl.L - pl.L1;
+  pl.R = rem < 7 ? rem : 7;
+  rem -= pl.R;
+  pl.nmid = 0;
+  while (rem > 0) {
+    const int m = rem < 7 ? rem : 7;
+    pl.mid[pl.nmid++] = m;
+    rem -= m;
+  }
+  pl.s0_hi = pl.L - pl.R;
+  if (pl.s0_hi + pl.R < LOG_TILE) pl.s0_hi = LOG_TILE - pl.R;   // B < 8192: the tile is just 8192 consecutive coordinates
+  return pl;
+}
+
+size_t partial_count(const thc_params* p, const Plan& pl) { return (size_t)p->n * (size_t)(p->d >> pl.L1); }
+
+size_t ws_x_bytes(const thc_params* p) { return (size_t)p->n * (size_t)p->d * sizeof(float); }
+
+uint64_t tiles_of(uint64_t d) { return (d + TILE - 1) / TILE; }
+
+int check_launch() { return hipGetLastError() == hipSuccess ? THC_OK : THC_ELAUNCH; }
+
+template <template <int> class Launcher, class... A>
+void dispatch_0_7(int r, A&&... args) {
+  switch (r) {
+    case 0: Launcher<0>::run(args...); break;
+    case 1: Launcher<1>::run(args...); break;
+    case 2: Launcher<2>::run(args...); break;
+    case 3: Launcher<3>::run(args...); break;
+    case 4: Launcher<4>::run(args...); break;
+    case 5: Launcher<5>::run(args...); break;
+    case 6: Launcher<6>::run(args...); break;
+    default: Launcher<7>::run(args...); break;
+  }
+}
+
+template <int R> struct LaunchMid {
+  static void run(const MidArgs& a, uint64_t tiles, hipStream_t s) { k_mid<R><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a); }
+};
+template <int R> struct LaunchQuant {
+  static void run(const QuantArgs& a, uint64_t tiles, hipStream_t s) { k_fwd_hi_quant<R><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a); }
+};
+template <int R> struct LaunchInvHi {
+  static void run(const InvHiArgs& a, uint64_t tiles, hipStream_t s) { k_inv_hi<R><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a); }
+};
+
+void launch_fwd_lo(int L1, const FwdLoArgs& a, uint64_t tiles, uint32_t n, hipStream_t s) {
+  const dim3 grid((unsigned)tiles, n), blk(NT);
+  switch (L1) {
+    case 10: k_fwd_lo<10><<<grid, blk, 0, s>>>(a); break;
+    case 11: k_fwd_lo<11><<<grid, blk, 0, s>>>(a); break;
+    case 12: k_fwd_lo<12><<<grid, blk, 0, s>>>(a); break;
+    default: k_fwd_lo<13><<<grid, blk, 0, s>>>(a); break;
+  }
+}
+
+void launch_inv_lo(int L1, const InvLoArgs& a, uint64_t tiles, hipStream_t s) {
+  const dim3 grid((unsigned)tiles), blk(NT);
+  switch (L1) {
+    case 10: k_inv_lo<10><<<grid, blk, 0, s>>>(a); break;
+    case 11: k_inv_lo<11><<<grid, blk, 0, s>>>(a); break;
+    case 12: k_inv_lo<12><<<grid, blk, 0, s>>>(a); break;
+    default: k_inv_lo<13><<<grid, blk, 0, s>>>(a); break;
+  }
+}
+
+// middle passes of one vector, ascending bits, in place
+void run_mids(const Plan& pl, float* x, uint64_t d, hipStream_t s) {
+  int s0 = pl.L1;
+  for (int m = 0; m < pl.nmid; ++m) {
+    MidArgs a{x, d, s0};
+    dispatch_0_7<LaunchMid>(pl.mid[m], a, tiles_of(d), s);
+    s0 += pl.mid[m];
+  }
+}
+
+// inverse transform of one vector that k_inv_lo is about to produce in `wsx`
+int run_inverse(const thc_params* p, const Plan& pl, const InvLoArgs& lo, float* wsx, InvHiArgs hi, hipStream_t s) {
+  launch_inv_lo(pl.L1, lo, tiles_of(p->d), s);
+  run_mids(pl, wsx, p->d, s);
+  hi.x = wsx;
+  hi.d = p->d;
+  hi.s0 = pl.s0_hi;
+  hi.c = (float)(1.0 / std::sqrt((double)p->block));
+  dispatch_0_7<LaunchInvHi>(pl.R, hi, tiles_of(p->d), s);
+  return check_launch();
+}
+
+const char* const kNames[] = {"THC_OK", "THC_EINVAL", "THC_ETABLE", "THC_EOVERFLOW", "THC_EUNSUPPORTED", "THC_ELAUNCH"};
+
+// standard normal helpers for the table solver
+double npdf(double a) { return std::exp(-0.5 * a * a) / std::sqrt(2.0 * M_PI); }
+double ncdf(double a) { return 0.5 * std::erfc(-a / std::sqrt(2.0)); }
+
+}  // namespace
+
+extern "C" {
+
+int thc_version(void) { return 100; }
+
+const char* thc_strerror(int status) {
+  const int i = -status;
+  return (i >= 0 && i <= 5) ? kNames[i] : "THC_E?";
+}
+
+int thc_workspace_bytes(const thc_params* p, size_t* bytes_out) {
+  const int rc = validate(p);
+  if (rc) return rc;
+  if (!bytes_out) return THC_EINVAL;
+  const Plan pl = make_plan(p->block);
+  *bytes_out = ws_x_bytes(p) + partial_count(p, pl) * sizeof(double) + 256;
+  return THC_OK;
+}
+
+int thc_prepare_range(const thc_params* p, uint64_t round, const void* const* grads, const float* const* ef,
+                      float* range_M, void* ws, void* stream) {
+  const int rc = validate(p);
+  if (rc) return rc;
+  if (!grads || !ws || !aligned16(ws) || round >> 32) return THC_EINVAL;
+  if (range_M && (reinterpret_cast<uintptr_t>(range_M) & 3u)) return THC_EINVAL;
+  FwdLoArgs a{};
+  for (uint32_t i = 0; i < p->n; ++i) {
+    if (!grads[i] || !aligned16(grads[i])) return THC_EINVAL;
+    a.grads.p[i] = grads[i];
+    if (ef) {
+      if (!ef[i] || !aligned16(ef[i])) return THC_EINVAL;
+      a.efs.p[i] = ef[i];
+    }
+  }
+  const Plan pl = make_plan(p->block);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  a.ws_x = static_cast<float*>(ws);
+  a.partials = reinterpret_cast<double*>(static_cast<char*>(ws) + ws_x_bytes(p));
+  a.d = p->d;
+  a.round = (uint32_t)round;
+  a.k0 = (uint32_t)p->seed;
+  a.k1 = (uint32_t)(p->seed >> 32);
+  a.bf16 = p->in_dtype == THC_DTYPE_BF16;
+  a.has_ef = ef != nullptr;
+  launch_fwd_lo(pl.L1, a, tiles_of(p->d), p->n, s);
+  if (range_M) {
+    RangeArgs r{a.partials, range_M, p->d, p->n, (uint32_t)pl.L, (uint32_t)pl.L1, p->t_p};
+    k_range<<<dim3((unsigned)(p->d / p->block)), dim3(64), 0, s>>>(r);
+  }
+  return check_launch();
+}
+
+int thc_compress(const thc_params* p, uint32_t worker_id, uint64_t round, const void* grad, float* ef_inout,
+                 const float* range_M, uint8_t* packed_out, void* ws, void* stream) {
+  const int rc = validate(p);
+  if (rc) return rc;
+  if (worker_id >= p->n || round >> 32 || !range_M || !packed_out || !ws) return THC_EINVAL;
+  if (!aligned16(packed_out) || !aligned16(ws)) return THC_EINVAL;
+  if (ef_inout && (!grad || !aligned16(grad) || !aligned16(ef_inout))) return THC_EINVAL;
+  const Plan pl = make_plan(p->block);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* wsx = static_cast<float*>(ws) + (size_t)worker_id * p->d;
+
+  run_mids(pl, wsx, p->d, s);
+
+  QuantArgs q{};
+  q.x = wsx;
+  q.range_M = range_M;
+  q.packed = packed_out;
+  q.d = p->d;
+  q.s0 = pl.s0_hi;
+  q.L = (uint32_t)pl.L;
+  q.b = p->b;
+  q.g = p->g;
+  q.round = (uint32_t)round;
+  q.worker = worker_id;
+  q.k0 = (uint32_t)p->seed;
+  q.k1 = (uint32_t)(p->seed >> 32);
+  q.c = (float)(1.0 / std::sqrt((double)p->block));
+  // per grid cell k: the largest index z0 with T[z0] <= k, its value lo and the gap wd to the next value
+  const uint32_t top = (1u << p->b) - 1;
+  for (uint32_t k = 0; k < 256; ++k) {
+    const uint32_t kk = k < p->g ? k : p->g;
+    uint32_t z0 = 0;
+    while (z0 < top && p->table[z0 + 1] <= kk) ++z0;
+    const uint32_t lo = p->table[z0];
+    const uint32_t wd = z0 < top ? (uint32_t)(p->table[z0 + 1] - lo) : 255u;   // 255: the top value never rounds up
+    q.lut[k] = lo | wd << 8 | z0 << 16;
+  }
+  dispatch_0_7<LaunchQuant>(pl.R, q, tiles_of(p->d), s);
+
+  if (ef_inout) {
+    InvLoArgs lo{};
+    lo.src = packed_out;
+    lo.range_M = range_M;
+    lo.ws_x = wsx;
+    lo.d = p->d;
+    lo.L = (uint32_t)pl.L;
+    lo.src_bits = p->b;
+    lo.use_table = 1;
+    lo.divisor = p->g;
+    std::memcpy(lo.table, p->table, 256);
+    InvHiArgs hi{};
+    hi.out = ef_inout;
+    hi.grad = grad;
+    hi.round = (uint32_t)round;
+    hi.k0 = q.k0;
+    hi.k1 = q.k1;
+    hi.mode = 1;
+    hi.bf16 = p->in_dtype == THC_DTYPE_BF16;
+    return run_inverse(p, pl, lo, wsx, hi, s);
+  }
+  return check_launch();
+}
+
+int thc_aggregate(const thc_params* p, const uint8_t* const* packed, void* agg_out, void* stream) {
+  const int rc = validate(p);
+  if (rc) return rc;
+  if (!packed || !agg_out || !aligned16(agg_out)) return THC_EINVAL;
+  for (uint32_t i = 0; i < p->n; ++i)
+    if (!packed[i] || !aligned16(packed[i])) return THC_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (p->b == 4 && p->agg_bits == 8) {
+    AggB4Args a{};
+    for (uint32_t i = 0; i < p->n; ++i) a.packed.p[i] = packed[i];
+    a.out = static_cast<uint8_t*>(agg_out);
+    a.nvec = p->d / 32;
+    a.n = p->n;
+    std::memcpy(a.tb, p->table, 16);
+    k_aggregate_b4w8<<<dim3((unsigned)((a.nvec + 255) / 256)), dim3(256), 0, s>>>(a);
+  } else {
+    AggArgs a{};
+    for (uint32_t i = 0; i < p->n; ++i) a.packed.p[i] = packed[i];
+    a.out = agg_out;
+    a.d = p->d;
+    a.n = p->n;
+    a.b = p->b;
+    a.agg_bits = p->agg_bits;
+    std::memcpy(a.table, p->table, 256);
+    const uint64_t threads = p->d / 16;
+    k_aggregate_generic<<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s>>>(a);
+  }
+  return check_launch();
+}
+
+int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const float* range_M, float* out,
+                   void* ws, void* stream) {
+  const int rc = validate(p);
+  if (rc) return rc;
+  if (round >> 32 || !agg || !range_M || !out || !ws) return THC_EINVAL;
+  if (!aligned16(agg) || !aligned16(out) || !aligned16(ws)) return THC_EINVAL;
+  const Plan pl = make_plan(p->block);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* wsx = static_cast<float*>(ws);
+  InvLoArgs lo{};
+  lo.src = agg;
+  lo.range_M = range_M;
+  lo.ws_x = wsx;
+  lo.d = p->d;
+  lo.L = (uint32_t)pl.L;
+  lo.src_bits = p->agg_bits;
+  lo.use_table = 0;
+  lo.divisor = p->g * p->n;
+  InvHiArgs hi{};
+  hi.out = out;
+  hi.round = (uint32_t)round;
+  hi.k0 = (uint32_t)p->seed;
+  hi.k1 = (uint32_t)(p->seed >> 32);
+  hi.mode = 0;
+  return run_inverse(p, pl, lo, wsx, hi, s);
+}
+
+double thc_threshold(double p) {
+  if (!(p > 0.0 && p < 1.0)) return NAN;
+  // solve ncdf(t) = 1 - p/2 for t >= 0, i.e. erfc(t / sqrt 2) = p: bisection, then Newton polish
+  double lo = 0.0, hi = 40.0;
+  for (int it = 0; it < 200; ++it) {
+    const double mid = 0.5 * (lo + hi);
+    if (std::erfc(mid / std::sqrt(2.0)) > p) lo = mid; else hi = mid;
+  }
+  double t = 0.5 * (lo + hi);
+  for (int it = 0; it < 3; ++it) {
+    const double f = std::erfc(t / std::sqrt(2.0)) - p;   // decreasing in t, derivative -2 pdf(t)
+    t += f / (2.0 * npdf(t));
+  }
+  return t;
+}
+
+int thc_solve_table(uint32_t b, uint32_t g, double p, uint8_t* table_out, double* cost_out) {
+  if (!table_out || b < 1 || b > 8 || g > 255 || g < (1u << b) - 1 || !(p > 0.0 && p < 1.0)) return THC_EINVAL;
+  const int L = (1 << b) - 1;   // edges of the path 0 -> g
+  const int G = (int)g;
+  const double tp = thc_threshold(p);
+  // Expected squared error of stochastic rounding between neighbours q0 < q1 of a standard normal:
+  // integral of (a - q0)(q1 - a) pdf(a) da, through the moments int pdf, int a pdf, int a^2 pdf.
+  std::vector<double> q(G + 1), Phi(G + 1), phi(G + 1);
+  for (int v = 0; v <= G; ++v) {
+    q[v] = -tp + v * (2.0 * tp / G);
+    Phi[v] = ncdf(q[v]);
+    phi[v] = npdf(q[v]);
+  }
+  auto edge = [&](int i, int j) {
+    const double m0 = Phi[j] - Phi[i];
+    const double m1 = -(phi[j] - phi[i]);
+    const double m2 = m0 - (q[j] * phi[j] - q[i] * phi[i]);
+    return -m2 + (q[i] + q[j]) * m1 - q[i] * q[j] * m0;
+  };
+  const double INF = HUGE_VAL;
+  std::vector<std::vector<double>> best(L + 1, std::vector<double>(G + 1, INF));   // best[e][v]: v -> g in e edges
+  best[0][G] = 0.0;
+  for (int e = 1; e <= L; ++e)
+    for (int v = 0; v <= G; ++v)
+      for (int u = v + 1; u <= G; ++u)
+        if (best[e - 1][u] < INF) {
+          const double c = edge(v, u) + best[e - 1][u];
+          if (c < best[e][v]) best[e][v] = c;
+        }
+  const double opt = best[L][0];
+  if (!(opt < INF)) return THC_EINVAL;
+  const double tol = std::fabs(opt) * 1e-12;
+  int v = 0;
+  double spent = 0.0;
+  table_out[0] = 0;
+  for (int e = L; e >= 1; --e) {
+    int pick = -1;
+    for (int u = v + 1; u <= G && pick < 0; ++u)
+      if (best[e - 1][u] < INF && spent + edge(v, u) + best[e - 1][u] <= opt + tol) pick = u;
+    if (pick < 0) return THC_EINVAL;
+    spent += edge(v, pick);
+    v = pick;
+    table_out[L - e + 1] = (uint8_t)v;
+  }
+  if (cost_out) *cost_out = opt;
+  return THC_OK;
+}
+
+}  // extern "C"

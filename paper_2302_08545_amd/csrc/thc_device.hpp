@@ -1,0 +1,135 @@
+// Device-side building blocks shared by the THC kernels (gfx950, wave64).
+//
+// Numeric contract: every butterfly is one binary32 add and one binary32 subtract, stages run in
+// ascending stride order, and nothing is contracted into a fused multiply-add unless written as
+// __builtin_fmaf.  The file must be compiled with -ffp-contract=off.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace thc {
+
+constexpr int LOG_TILE = 13;
+constexpr int TILE = 1 << LOG_TILE;   // coordinates one workgroup holds in LDS (32 KB of binary32)
+constexpr int NT = 512;               // threads per workgroup: 16 coordinates each
+constexpr int MAXW = 64;              // THC_MAX_WORKERS
+
+struct PtrArr {
+  const void* p[MAXW];
+};
+
+// ---------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11).  One call yields 128 bits.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n1 = (uint32_t)p1;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    const uint32_t n3 = (uint32_t)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return make_uint4(c0, c1, c2, c3);
+}
+
+constexpr uint32_t SIGN_STREAM = 0x80000000u;
+
+// Word `(j >> 5) & 3` of the sign stream call that covers coordinate j (j a multiple of 32).
+__device__ __forceinline__ uint32_t sign_word(uint64_t j, uint32_t round, uint32_t k0, uint32_t k1) {
+  const uint64_t q = j >> 7;
+  const uint4 r = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), round, SIGN_STREAM, k0, k1);
+  const uint32_t sel = (uint32_t)(j >> 5) & 3u;
+  return sel == 0 ? r.x : sel == 1 ? r.y : sel == 2 ? r.z : r.w;
+}
+
+__device__ __forceinline__ float flip(float x, uint32_t bit /* 0 or 1 */) {
+  return __uint_as_float(__float_as_uint(x) ^ (bit << 31));
+}
+
+// ---------------------------------------------------------------------------------------------
+// In-register Walsh-Hadamard butterflies over 2^NB values, strides 1, 2, 4, ... in that order.
+// ---------------------------------------------------------------------------------------------
+template <int NB>
+__device__ __forceinline__ void bfly(float (&v)[1 << NB]) {
+#pragma unroll
+  for (int s = 0; s < NB; ++s) {
+    const int h = 1 << s;
+#pragma unroll
+    for (int j = 0; j < (1 << NB); ++j) {
+      if ((j & h) == 0) {
+        const float a = v[j], b = v[j + h];
+        v[j] = a + b;
+        v[j + h] = a - b;
+      }
+    }
+  }
+}
+
+template <>
+__device__ __forceinline__ void bfly<0>(float (&)[1]) {}
+
+__device__ __forceinline__ void bfly_f4(float4& x) {   // strides 1 and 2 inside four consecutive values
+  const float a = x.x + x.y, b = x.x - x.y, c = x.z + x.w, d = x.z - x.w;
+  x.x = a + c; x.y = b + d; x.z = a - c; x.w = b - d;
+}
+
+// ---------------------------------------------------------------------------------------------
+// LDS tile of TILE floats.  Logical index -> physical slot: bits 2..4 are XORed with bits 6..8 so that
+// the strided gathers of every round hit 32 distinct banks per half-wave; bits 0..1 are untouched, so a
+// group of four consecutive, 4-aligned values stays a 16-byte unit.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ int swz(int i) { return i ^ (((i >> 6) & 7) << 2); }
+
+// One round: every thread gathers 16 values as (16 >> NB) groups of 2^NB values that differ in index
+// bits [P, P+NB), runs the butterflies, and hands each result to sink(index, value).
+template <int P, int NB, class Sink>
+__device__ __forceinline__ void lds_round(const float* lds, int t, Sink&& sink) {
+  constexpr int E = 1 << NB;
+  constexpr int G = 16 >> NB;
+#pragma unroll
+  for (int gi = 0; gi < G; ++gi) {
+    const int vt = t + NT * gi;
+    const int base = (vt & ((1 << P) - 1)) | ((vt >> P) << (P + NB));
+    float v[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) v[e] = lds[swz(base + (e << P))];
+    bfly<NB>(v);
+#pragma unroll
+    for (int e = 0; e < E; ++e) sink(base + (e << P), v[e]);
+  }
+}
+
+// Stages for index bits [P, HI) on a tile resident in LDS.  When FUSE is set the last round hands its
+// results to `sink` (typically a global store) instead of writing them back to LDS.
+template <int P, int HI, bool FUSE, class Sink>
+__device__ __forceinline__ void lds_stages(float* lds, int t, Sink&& sink) {
+  constexpr int NB = (HI - P) < 4 ? (HI - P) : 4;
+  constexpr bool LAST = (P + NB == HI);
+  __syncthreads();
+  if constexpr (LAST && FUSE) {
+    lds_round<P, NB>(lds, t, sink);
+  } else {
+    if constexpr (NB > 0) {
+      lds_round<P, NB>(lds, t, [&](int i, float v) { lds[swz(i)] = v; });
+    }
+    if constexpr (!LAST) lds_stages<P + NB, HI, FUSE>(lds, t, sink);
+  }
+}
+
+// fixed-order butterfly sum over the 64 lanes of a wave; every lane ends with the same total
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m, 64);
+  return v;
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+}  // namespace thc

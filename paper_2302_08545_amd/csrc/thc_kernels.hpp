@@ -1,0 +1,560 @@
+// THC hot-path kernels for gfx950.  See include/thc.h for the conventions (streams, bit order, RNG).
+//
+// A Hadamard transform of a block of B = 2^L coordinates is split by index bits:
+//   "lo"  pass: bits [0, L1), L1 = min(L, 13): one workgroup owns 8192 consecutive coordinates
+//   "mid" pass: (only for L > 20) up to 7 more bits, in place in the workspace
+//   "hi"  pass: the remaining top bits (at most 7): one workgroup owns 2^R rows, 8192 >> R consecutive
+//               coordinates wide, rows 2^S0 coordinates apart
+// Bits are always processed in ascending order, so the rounding of every butterfly is fixed.
+#pragma once
+
+#include "thc_device.hpp"
+
+namespace thc {
+
+// ---------------------------------------------------------------------------------------------
+// Forward "lo" pass (Alg. 3: x = grad + e; ||x||; first part of R = RHT(x) with the diagonal D^r).
+// grid = (tiles, n workers).  Writes the half-rotated tile to ws_x[worker] and one partial sum of
+// squares per min(B, 8192) coordinates.
+// ---------------------------------------------------------------------------------------------
+struct FwdLoArgs {
+  PtrArr grads;
+  PtrArr efs;          // unused when !has_ef
+  float* ws_x;         // n * d floats
+  double* partials;    // n * (d >> min(L, 13)) doubles
+  uint64_t d;
+  uint32_t round, k0, k1;
+  uint32_t bf16, has_ef;
+};
+
+template <int L1>
+__global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
+  __shared__ __align__(16) float lds[TILE];
+  __shared__ uint32_t sgn[TILE / 32];
+  __shared__ double wsum[4][NT / 64];
+
+  const int t = threadIdx.x;
+  const uint32_t worker = blockIdx.y;
+  const uint64_t off = (uint64_t)blockIdx.x * TILE;
+
+  if (t < 64) {   // the tile's 8192 diagonal entries: 64 Philox calls of 128 bits
+    const uint64_t q = (off >> 7) + t;
+    const uint4 r = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, SIGN_STREAM, a.k0, a.k1);
+    *reinterpret_cast<uint4*>(&sgn[4 * t]) = r;
+  }
+
+  float4 x[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint64_t j = off + 4u * (uint32_t)(i * NT + t);
+    x[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (j < a.d) {
+      if (a.bf16) {
+        const ushort4 h = *reinterpret_cast<const ushort4*>(static_cast<const uint16_t*>(a.grads.p[worker]) + j);
+        x[i] = make_float4(bf16_to_f32(h.x), bf16_to_f32(h.y), bf16_to_f32(h.z), bf16_to_f32(h.w));
+      } else {
+        x[i] = *reinterpret_cast<const float4*>(static_cast<const float*>(a.grads.p[worker]) + j);
+      }
+      if (a.has_ef) {
+        const float4 e = *reinterpret_cast<const float4*>(static_cast<const float*>(a.efs.p[worker]) + j);
+        x[i].x += e.x; x[i].y += e.y; x[i].z += e.z; x[i].w += e.w;
+      }
+    }
+  }
+  __syncthreads();
+
+  // sum of squares in binary64 (a binary32 square is exact there)
+  double acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const double p = (double)x[i].x, q = (double)x[i].y, r = (double)x[i].z, s = (double)x[i].w;
+    acc[i] = __builtin_fma(s, s, __builtin_fma(r, r, __builtin_fma(q, q, p * p)));
+  }
+  // a thread's four float4 sit 2048 coordinates apart: they share a block only if the block is that large
+  const int wave = t >> 6, lane = t & 63;
+  if constexpr (L1 >= 13) {
+    const double s = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+    if (lane == 0) wsum[0][wave] = s;
+  } else if constexpr (L1 == 12) {
+    const double s0 = wave_sum(acc[0] + acc[1]), s1 = wave_sum(acc[2] + acc[3]);
+    if (lane == 0) { wsum[0][wave] = s0; wsum[1][wave] = s1; }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const double s = wave_sum(acc[i]);
+      if (lane == 0) wsum[i][wave] = s;
+    }
+  }
+
+  // diagonal, strides 1 and 2, then into LDS
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int idx = 4 * (i * NT + t);
+    const uint32_t bits = sgn[idx >> 5] >> (idx & 31);
+    x[i].x = flip(x[i].x, bits & 1u);
+    x[i].y = flip(x[i].y, (bits >> 1) & 1u);
+    x[i].z = flip(x[i].z, (bits >> 2) & 1u);
+    x[i].w = flip(x[i].w, (bits >> 3) & 1u);
+    bfly_f4(x[i]);
+    *reinterpret_cast<float4*>(&lds[swz(idx)]) = x[i];
+  }
+
+  float* dst = a.ws_x + (uint64_t)worker * a.d + off;
+  const uint64_t left = a.d - off;   // coordinates of this tile that exist (tail tile of a short vector)
+  lds_stages<2, L1, true>(lds, t, [&](int i, float v) {
+    if ((uint64_t)i < left) dst[i] = v;
+  });
+
+  // partial sums: one per block of 2^L1 coordinates inside the tile, combined in a fixed order.
+  // (the __syncthreads inside lds_stages made wsum visible)
+  constexpr int NBLK = TILE >> L1;
+  if (t < NBLK) {
+    double s = 0.0;
+    if constexpr (L1 >= 13) {
+#pragma unroll
+      for (int w = 0; w < 8; ++w) s += wsum[0][w];
+    } else if constexpr (L1 == 12 || L1 == 11) {
+#pragma unroll
+      for (int w = 0; w < 8; ++w) s += wsum[t][w];
+    } else {   // L1 == 10: block = 2 * i + (wave >> 2)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) s += wsum[t >> 1][4 * (t & 1) + w];
+    }
+    const uint64_t pidx = (off >> L1) + t;
+    if (pidx < (a.d >> L1)) a.partials[(uint64_t)worker * (a.d >> L1) + pidx] = s;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Range (Sec. 5.3; Alg. 3: M = (t_p / sqrt(d)) * max_i ||x_i||, per block).  One wave per block.
+// ---------------------------------------------------------------------------------------------
+struct RangeArgs {
+  const double* partials;   // n * (d >> L1)
+  float* range_M;           // K
+  uint64_t d;
+  uint32_t n, L, L1;
+  float t_p;
+};
+
+__global__ __launch_bounds__(64) void k_range(const RangeArgs a) {
+  const uint64_t k = blockIdx.x;
+  const int lane = threadIdx.x;
+  const uint32_t ppb = 1u << (a.L - a.L1);           // partials per block
+  const uint64_t per_worker = a.d >> a.L1;
+  double smax = 0.0;
+  for (uint32_t i = 0; i < a.n; ++i) {
+    const double* p = a.partials + (uint64_t)i * per_worker + k * ppb;
+    double s = 0.0;
+    for (uint32_t j = lane; j < ppb; j += 64) s += p[j];
+    s = wave_sum(s);
+    smax = s > smax ? s : smax;
+  }
+  if (lane == 0) {
+    const double M = ((double)a.t_p * __builtin_sqrt(smax)) / __builtin_sqrt((double)(1ull << a.L));
+    a.range_M[k] = (float)M;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Shared addressing of the strided passes.  A tile is 2^R rows by W = 8192 >> R columns; rows are
+// 2^S0 coordinates apart; 2^(S0+R-13) tiles side by side cover one span of 2^(S0+R) coordinates.
+// ---------------------------------------------------------------------------------------------
+template <int R>
+struct HiGeom {
+  static constexpr int LOGW = LOG_TILE - R;
+  static constexpr int W = 1 << LOGW;
+  uint64_t base;   // coordinate of (row 0, col 0)
+  int s0;
+  __device__ HiGeom(uint64_t tile, int s0_) : s0(s0_) {
+    const int lt = s0_ + R - LOG_TILE;                  // log2(tiles per span), >= 0
+    const uint64_t span = tile >> lt, ct = tile & ((1ull << lt) - 1);
+    base = (span << (s0_ + R)) + ct * W;
+  }
+  __device__ uint64_t coord(int idx) const {
+    return base + ((uint64_t)(idx >> LOGW) << s0) + (uint32_t)(idx & (W - 1));
+  }
+};
+
+template <int R>
+__device__ __forceinline__ void hi_load_to_lds(const float* src, const HiGeom<R>& g, uint64_t d, float* lds, int t) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int idx = 4 * (i * NT + t);
+    const uint64_t j = g.coord(idx);
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (j < d) v = *reinterpret_cast<const float4*>(src + j);
+    *reinterpret_cast<float4*>(&lds[swz(idx)]) = v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// "mid" pass: R more bits, in place.
+// ---------------------------------------------------------------------------------------------
+struct MidArgs {
+  float* x;   // d floats (one worker's half-rotated vector)
+  uint64_t d;
+  int s0;
+};
+
+template <int R>
+__global__ __launch_bounds__(NT) void k_mid(const MidArgs a) {
+  __shared__ __align__(16) float lds[TILE];
+  const int t = threadIdx.x;
+  const HiGeom<R> g(blockIdx.x, a.s0);
+  hi_load_to_lds<R>(a.x, g, a.d, lds, t);
+  lds_stages<LOG_TILE - R, LOG_TILE, false>(lds, t, [](int, float) {});
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int idx = 4 * (i * NT + t);
+    const uint64_t j = g.coord(idx);
+    if (j < a.d) *reinterpret_cast<float4*>(a.x + j) = *reinterpret_cast<const float4*>(&lds[swz(idx)]);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Forward "hi" pass + main stage, worker side (Alg. 3: R = RHT(x) finished; clamp to [-M, M];
+// stochastic quantization onto the table's values (Sec. 4.1); Z = T^-1[Y] (Alg. 2); bit-pack).
+//
+// Per coordinate, in binary32:  v = h * c;  x' = med(v, -M, M);  y16 = (x' + M) * (scale * 2^16);
+// k = floor(y16 / 2^16);  (lo, wd, z0) = LUT[k];  t16 = y16 - lo * 2^16;
+// up iff (half + 1/2) * wd < t16  (one fused multiply-add, then compare);  z = z0 + up.
+// The top table entry carries wd = 255 so that it can never round up.
+// ---------------------------------------------------------------------------------------------
+struct QuantArgs {
+  const float* x;          // one worker's half-rotated vector, d floats
+  const float* range_M;    // K floats
+  uint8_t* packed;         // d*b/8 bytes
+  uint64_t d;
+  int s0;                  // log2 of the row pitch
+  uint32_t L;              // log2 B
+  uint32_t b, g;
+  uint32_t round, worker, k0, k1;
+  float c;                 // 1/sqrt(B)
+  uint32_t lut[256];       // per grid cell k: lo | wd << 8 | z0 << 16
+};
+
+template <int R>
+__global__ __launch_bounds__(NT) void k_fwd_hi_quant(const QuantArgs a) {
+  __shared__ __align__(16) float lds[TILE];
+  __shared__ uint32_t lut[256];
+  __shared__ float sM[8], sScale[8];
+
+  const int t = threadIdx.x;
+  const HiGeom<R> g(blockIdx.x, a.s0);
+
+  if (t < 256) lut[t] = a.lut[t];
+  // per-block scalars; a tile spans more than one block only when B < 8192 (then R == 0)
+  const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
+  if (t < nblk) {
+    const uint64_t blk = (g.base >> a.L) + t;
+    float M = 0.f;
+    if (blk < (a.d >> a.L)) M = a.range_M[blk];
+    sM[t] = M;
+    sScale[t] = M > 0.f ? (float)((double)a.g / (2.0 * (double)M)) * 65536.0f : 0.f;
+  }
+
+  hi_load_to_lds<R>(a.x, g, a.d, lds, t);
+  lds_stages<LOG_TILE - R, LOG_TILE, false>(lds, t, [](int, float) {});
+  __syncthreads();
+
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int idx = 8 * (t + NT * h);
+    const uint64_t j = g.coord(idx);
+    if (j >= a.d) continue;
+    const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
+    const float M = sM[bt], sc = sScale[bt], negM = -M;
+    const float4 p0 = *reinterpret_cast<const float4*>(&lds[swz(idx)]);
+    const float4 p1 = *reinterpret_cast<const float4*>(&lds[swz(idx + 4)]);
+    const float hv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+    const uint64_t q = j >> 3;
+    const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, a.worker, a.k0, a.k1);
+    const uint32_t rw[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
+    uint32_t z[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float v = hv[e] * a.c;
+      const float xc = __builtin_fminf(__builtin_fmaxf(v, negM), M);
+      const float y16 = (xc + M) * sc;
+      const uint32_t ki = (uint32_t)y16;
+      const uint32_t ent = lut[(ki >> 16) & 255u];
+      const float lo = (float)(ent & 255u), wd = (float)((ent >> 8) & 255u);
+      const float t16 = __builtin_fmaf(lo, -65536.0f, y16);
+      const float hf = (float)((e & 1) ? (rw[e >> 1] >> 16) : (rw[e >> 1] & 0xFFFFu));
+      const float prod = __builtin_fmaf(hf, wd, 0.5f * wd);
+      z[e] = (ent >> 16) + (prod < t16 ? 1u : 0u);
+    }
+    if (a.b == 4) {
+      uint32_t w = 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) w |= z[e] << (4 * e);
+      *reinterpret_cast<uint32_t*>(a.packed + (j >> 1)) = w;
+    } else if (a.b == 2) {
+      uint32_t w = 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) w |= z[e] << (2 * e);
+      *reinterpret_cast<uint16_t*>(a.packed + (j >> 2)) = (uint16_t)w;
+    } else if (a.b == 8) {
+      const uint32_t w0 = z[0] | z[1] << 8 | z[2] << 16 | z[3] << 24;
+      const uint32_t w1 = z[4] | z[5] << 8 | z[6] << 16 | z[7] << 24;
+      *reinterpret_cast<uint2*>(a.packed + j) = make_uint2(w0, w1);
+    } else {
+      uint32_t w = 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) w |= z[e] << e;
+      a.packed[j >> 3] = (uint8_t)w;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Inverse "lo" pass.  Source is either the aggregated stream (decompression, Alg. 2:
+// m + (Y/n)(M-m)/g = Y * step_n - M) or one worker's packed indices (error feedback, Alg. 3:
+// X_i = m + T[z](M-m)/g = T[z] * step_g - M).  One thread loads 16 consecutive coordinates.
+// ---------------------------------------------------------------------------------------------
+struct InvLoArgs {
+  const void* src;         // aggregated stream or packed indices
+  const float* range_M;
+  float* ws_x;             // d floats, written
+  uint64_t d;
+  uint32_t L;
+  uint32_t src_bits;       // bits per coordinate in src
+  uint32_t use_table;      // 1: src holds table indices; 0: src holds aggregated table values
+  uint32_t divisor;        // g*n (aggregated) or g (indices)
+  uint8_t table[256];
+};
+
+template <int L1>
+__global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
+  __shared__ __align__(16) float lds[TILE];
+  __shared__ float sM[8], sStep[8];
+  __shared__ float tabf[256];
+
+  const int t = threadIdx.x;
+  const uint64_t off = (uint64_t)blockIdx.x * TILE;
+  const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
+  if (t < nblk) {
+    const uint64_t blk = (off >> a.L) + t;
+    float M = 0.f;
+    if (blk < (a.d >> a.L)) M = a.range_M[blk];
+    sM[t] = M;
+    sStep[t] = (float)((2.0 * (double)M) / (double)a.divisor);
+  }
+  if (a.use_table && t < 256) tabf[t] = (float)a.table[t];
+  __syncthreads();
+
+  const int idx = 16 * t;
+  const uint64_t j = off + idx;
+  float v[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) v[e] = 0.f;
+  if (j < a.d) {
+    uint32_t y[16];
+    const uint8_t* s8 = static_cast<const uint8_t*>(a.src);
+    if (a.src_bits == 8) {
+      const uint4 r = *reinterpret_cast<const uint4*>(s8 + j);
+      const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+      for (int e = 0; e < 16; ++e) y[e] = (w[e >> 2] >> (8 * (e & 3))) & 255u;
+    } else if (a.src_bits == 16) {
+      const uint4 r0 = *reinterpret_cast<const uint4*>(s8 + 2 * j);
+      const uint4 r1 = *reinterpret_cast<const uint4*>(s8 + 2 * j + 16);
+      const uint32_t w[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+#pragma unroll
+      for (int e = 0; e < 16; ++e) y[e] = (w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+    } else if (a.src_bits == 4) {
+      const uint2 r = *reinterpret_cast<const uint2*>(s8 + (j >> 1));
+      const uint32_t w[2] = {r.x, r.y};
+#pragma unroll
+      for (int e = 0; e < 16; ++e) y[e] = (w[e >> 3] >> (4 * (e & 7))) & 15u;
+    } else if (a.src_bits == 2) {
+      const uint32_t w = *reinterpret_cast<const uint32_t*>(s8 + (j >> 2));
+#pragma unroll
+      for (int e = 0; e < 16; ++e) y[e] = (w >> (2 * e)) & 3u;
+    } else {
+      const uint32_t w = *reinterpret_cast<const uint16_t*>(s8 + (j >> 3));
+#pragma unroll
+      for (int e = 0; e < 16; ++e) y[e] = (w >> e) & 1u;
+    }
+    const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
+    const float negM = -sM[bt], step = sStep[bt];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const float f = a.use_table ? tabf[y[e]] : (float)y[e];
+      v[e] = f * step + negM;
+    }
+  }
+  bfly<4>(v);
+#pragma unroll
+  for (int e = 0; e < 16; e += 4)
+    *reinterpret_cast<float4*>(&lds[swz(idx + e)]) = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
+
+  float* dst = a.ws_x + off;
+  const uint64_t left = a.d - off;
+  lds_stages<4, L1, true>(lds, t, [&](int i, float val) {
+    if ((uint64_t)i < left) dst[i] = val;
+  });
+}
+
+// ---------------------------------------------------------------------------------------------
+// Inverse "hi" pass: finish H, scale by 1/sqrt(B), apply the diagonal (Sec. 5.1: RHT^-1 = D H / sqrt(d)).
+// mode 0: out = result (Alg. 3, the global update);
+// mode 1: e <- (grad + e) - result (Alg. 3, error-feedback update), out = ef buffer, read and written.
+// ---------------------------------------------------------------------------------------------
+struct InvHiArgs {
+  const float* x;      // half-rotated vector, d floats
+  float* out;          // d floats
+  const void* grad;    // mode 1 only
+  uint64_t d;
+  int s0;
+  uint32_t round, k0, k1;
+  uint32_t mode, bf16;
+  float c;
+};
+
+template <int R>
+__global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
+  __shared__ __align__(16) float lds[TILE];
+  __shared__ uint32_t sgn[TILE / 32];
+
+  const int t = threadIdx.x;
+  const HiGeom<R> g(blockIdx.x, a.s0);
+
+  if (t < TILE / 32) sgn[t] = sign_word(g.coord(32 * t), a.round, a.k0, a.k1);
+
+  hi_load_to_lds<R>(a.x, g, a.d, lds, t);
+  lds_stages<LOG_TILE - R, LOG_TILE, false>(lds, t, [](int, float) {});
+  __syncthreads();
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int idx = 4 * (i * NT + t);
+    const uint64_t j = g.coord(idx);
+    if (j >= a.d) continue;
+    float4 v = *reinterpret_cast<const float4*>(&lds[swz(idx)]);
+    const uint32_t bits = sgn[idx >> 5] >> (idx & 31);
+    v.x = flip(v.x * a.c, bits & 1u);
+    v.y = flip(v.y * a.c, (bits >> 1) & 1u);
+    v.z = flip(v.z * a.c, (bits >> 2) & 1u);
+    v.w = flip(v.w * a.c, (bits >> 3) & 1u);
+    if (a.mode == 1) {
+      float4 x;
+      if (a.bf16) {
+        const ushort4 h = *reinterpret_cast<const ushort4*>(static_cast<const uint16_t*>(a.grad) + j);
+        x = make_float4(bf16_to_f32(h.x), bf16_to_f32(h.y), bf16_to_f32(h.z), bf16_to_f32(h.w));
+      } else {
+        x = *reinterpret_cast<const float4*>(static_cast<const float*>(a.grad) + j);
+      }
+      const float4 e = *reinterpret_cast<const float4*>(a.out + j);
+      x.x += e.x; x.y += e.y; x.z += e.z; x.w += e.w;
+      v = make_float4(x.x - v.x, x.y - v.y, x.z - v.z, x.w - v.w);
+    }
+    *reinterpret_cast<float4*>(a.out + j) = v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Aggregation (Alg. 2: Y = sum_i T[Z_i]; the PS only looks up and adds).  Generic path: one thread
+// owns 16 consecutive coordinates of every stream; table in LDS.
+// ---------------------------------------------------------------------------------------------
+struct AggArgs {
+  PtrArr packed;
+  void* out;
+  uint64_t d;
+  uint32_t n, b, agg_bits;
+  uint8_t table[256];
+};
+
+__global__ __launch_bounds__(256) void k_aggregate_generic(const AggArgs a) {
+  __shared__ uint32_t tab[256];
+  tab[threadIdx.x] = a.table[threadIdx.x];
+  __syncthreads();
+  const uint64_t j = ((uint64_t)blockIdx.x * 256 + threadIdx.x) * 16;
+  if (j >= a.d) return;
+  uint32_t acc[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0;
+  for (uint32_t i = 0; i < a.n; ++i) {
+    const uint8_t* s8 = static_cast<const uint8_t*>(a.packed.p[i]);
+    if (a.b == 4) {
+      const uint2 r = *reinterpret_cast<const uint2*>(s8 + (j >> 1));
+      const uint32_t w[2] = {r.x, r.y};
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[e] += tab[(w[e >> 3] >> (4 * (e & 7))) & 15u];
+    } else if (a.b == 2) {
+      const uint32_t w = *reinterpret_cast<const uint32_t*>(s8 + (j >> 2));
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[e] += tab[(w >> (2 * e)) & 3u];
+    } else if (a.b == 8) {
+      const uint4 r = *reinterpret_cast<const uint4*>(s8 + j);
+      const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[e] += tab[(w[e >> 2] >> (8 * (e & 3))) & 255u];
+    } else {
+      const uint32_t w = *reinterpret_cast<const uint16_t*>(s8 + (j >> 3));
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[e] += tab[(w >> e) & 1u];
+    }
+  }
+  if (a.agg_bits == 8) {
+    uint32_t w[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) w[k] = acc[4 * k] | acc[4 * k + 1] << 8 | acc[4 * k + 2] << 16 | acc[4 * k + 3] << 24;
+    *reinterpret_cast<uint4*>(static_cast<uint8_t*>(a.out) + j) = make_uint4(w[0], w[1], w[2], w[3]);
+  } else {
+    uint32_t w[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) w[k] = acc[2 * k] | acc[2 * k + 1] << 16;
+    uint4* o = reinterpret_cast<uint4*>(static_cast<uint8_t*>(a.out) + 2 * j);
+    o[0] = make_uint4(w[0], w[1], w[2], w[3]);
+    o[1] = make_uint4(w[4], w[5], w[6], w[7]);
+  }
+}
+
+// 4-bit indices -> 8-bit sums, the paper's prototype widths (Sec. 3).  One thread owns 32 coordinates
+// (16 bytes of every stream); the 16-entry table sits in four registers and is applied to four
+// nibbles at a time with byte permutes; sums of four coordinates share a register (no carry can
+// cross a byte because g*n <= 255).
+struct AggB4Args {
+  PtrArr packed;
+  uint8_t* out;
+  uint64_t nvec;    // d / 32
+  uint32_t n;
+  uint32_t tb[4];   // table bytes 0..15, little endian
+};
+
+__device__ __forceinline__ uint32_t lut16x4(uint32_t sel, const uint32_t (&tb)[4]) {
+  const uint32_t s7 = sel & 0x07070707u;
+  const uint32_t lo = __builtin_amdgcn_perm(tb[1], tb[0], s7);
+  const uint32_t hi = __builtin_amdgcn_perm(tb[3], tb[2], s7);
+  const uint32_t m = ((sel & 0x08080808u) >> 3) * 0xFFu;
+  return (hi & m) | (lo & ~m);
+}
+
+__global__ __launch_bounds__(256) void k_aggregate_b4w8(const AggB4Args a) {
+  const uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (v >= a.nvec) return;
+  const uint32_t tb[4] = {a.tb[0], a.tb[1], a.tb[2], a.tb[3]};
+  uint32_t ev[4] = {0, 0, 0, 0}, od[4] = {0, 0, 0, 0};
+  for (uint32_t i = 0; i < a.n; ++i) {
+    const uint4 r = reinterpret_cast<const uint4*>(a.packed.p[i])[v];
+    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      ev[k] += lut16x4(w[k] & 0x0F0F0F0Fu, tb);          // coordinates 8k + 0, 2, 4, 6
+      od[k] += lut16x4((w[k] >> 4) & 0x0F0F0F0Fu, tb);   // coordinates 8k + 1, 3, 5, 7
+    }
+  }
+  uint32_t o[8];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    o[2 * k] = __builtin_amdgcn_perm(od[k], ev[k], 0x05010400u);
+    o[2 * k + 1] = __builtin_amdgcn_perm(od[k], ev[k], 0x07030602u);
+  }
+  uint4* dst = reinterpret_cast<uint4*>(a.out + v * 32);
+  dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
+  dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
+}
+
+}  // namespace thc

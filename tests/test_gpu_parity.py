@@ -1,0 +1,396 @@
+"""Parity of the HIP library (through the C-ABI binding) against the CPU oracle, element by element,
+on the same seeded inputs.  Bars (written here, derived in the design doc):
+  * packed bytes, aggregated sums: bit-exact, except that at most 1e-6 of the indices may differ, by one
+    level, where a value sits within an ulp of a rounding threshold (expected: none);
+  * float outputs (decompressed average, error-feedback buffers): relative L2 error <= 1e-5
+    (expected: bit-identical, the butterfly order is fixed);
+  * range M: relative error <= 2^-23 (binary64 sums in a different order, rounded once to binary32).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import thc_oracle as o
+from paper_2302_08545_amd import api
+from paper_2302_08545_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+SEED = wl.RHT_SEED
+F32 = np.float32
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    api.lib()
+    yield
+    torch.cuda.synchronize()
+
+
+def table_for(b, g, p=1 / 32):
+    return o.solve_table(b, g, p)
+
+
+def both_params(d, block, n, b=4, g=30, agg_bits=8, p=1 / 32, bf16=False, seed=SEED, table=None):
+    T = table if table is not None else table_for(b, g, p)
+    tp = o.t_p_of(p)
+    P = o.Params(d=d, block=block, n=n, b=b, g=g, t_p=tp, seed=seed, table=T, agg_bits=agg_bits)
+    L = api.make_params(d, block, n, b, g, tp, seed, T, agg_bits, api.THC_DTYPE_BF16 if bf16 else api.THC_DTYPE_F32)
+    return P, L
+
+
+def rel_l2(a, b):
+    a = a.astype(np.float64)
+    b = b.astype(np.float64)
+    nb = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / nb) if nb > 0 else float(np.linalg.norm(a))
+
+
+def assert_indices_match(gpu_packed, ref_packed, b, label=""):
+    if np.array_equal(gpu_packed, ref_packed):
+        return
+    zg = o.unpack_indices(gpu_packed, b).astype(np.int64)
+    zr = o.unpack_indices(ref_packed, b).astype(np.int64)
+    diff = zg != zr
+    assert diff.mean() <= 1e-6 and np.abs(zg - zr).max() <= 1, \
+        f"{label}: {diff.sum()} of {diff.size} indices differ, max step {np.abs(zg - zr).max()}"
+
+
+class GpuRound:
+    """Device buffers for one configuration and the four calls on them."""
+
+    def __init__(self, L, ef=False):
+        self.L = L
+        d, n = L.d, L.n
+        self.K = d // L.block
+        self.ws = torch.empty(api.thc_workspace_bytes(L), dtype=torch.uint8, device=DEV)
+        self.range_M = torch.zeros(self.K, dtype=torch.float32, device=DEV)
+        self.packed = [torch.zeros(d * L.b // 8, dtype=torch.uint8, device=DEV) for _ in range(n)]
+        self.agg = torch.zeros(d * L.agg_bits // 8, dtype=torch.uint8, device=DEV)
+        self.out = torch.zeros(d, dtype=torch.float32, device=DEV)
+        self.efs = [torch.zeros(d, dtype=torch.float32, device=DEV) for _ in range(n)] if ef else None
+
+    def prepare(self, rnd, grads, with_range=True):
+        api.thc_prepare_range(self.L, rnd, grads, self.efs, self.range_M if with_range else None, self.ws)
+
+    def compress_all(self, rnd, grads, range_M=None):
+        rm = self.range_M if range_M is None else range_M
+        for i in range(self.L.n):
+            api.thc_compress(self.L, i, rnd, grads[i], None if self.efs is None else self.efs[i], rm,
+                             self.packed[i], self.ws)
+
+    def aggregate(self):
+        api.thc_aggregate(self.L, self.packed, self.agg)
+
+    def decompress(self, rnd, range_M=None):
+        api.thc_decompress(self.L, rnd, self.agg, self.range_M if range_M is None else range_M, self.out, self.ws)
+
+    def agg_numpy(self):
+        a = self.agg.cpu().numpy()
+        return a if self.L.agg_bits == 8 else a.view(np.uint16)
+
+
+def make_grads(d, n, scale=1e-3, seed=1, bf16=False):
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    out = []
+    for i in range(n):
+        t = torch.randn(d, generator=g, dtype=torch.float32) * (scale * (1 + 0.3 * i))
+        if bf16:
+            t = t.to(torch.bfloat16)
+        out.append(t)
+    return out
+
+
+def to_np32(t):
+    return t.to(torch.float32).cpu().numpy()
+
+
+# ----------------------------------------------------------------------------- individual calls
+@pytest.mark.parametrize("block,K,n", [(1 << 10, 3, 2), (1 << 11, 5, 2), (1 << 12, 4, 3), (1 << 13, 3, 2),
+                                       (1 << 15, 2, 2), (1 << 20, 2, 4)])
+def test_prepare_range_and_compress(block, K, n):
+    d = block * K
+    P, L = both_params(d, block, n)
+    grads = make_grads(d, n, seed=block + K)
+    grads[0][:block] *= 30.0                     # a block where one worker dominates the norm
+    R = GpuRound(L)
+    dg = [g.to(DEV) for g in grads]
+    R.prepare(4, dg)
+    M_ref = o.prepare_range(P, [to_np32(g) for g in grads])
+    M_gpu = R.range_M.cpu().numpy()
+    assert np.all(np.abs(M_gpu - M_ref) <= np.abs(M_ref) * 2.0 ** -23), (M_gpu, M_ref)
+    # the oracle's range goes into the GPU's compress, so a last-bit difference in M cannot hide anything
+    R.compress_all(4, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+    for i in range(n):
+        ref, _ = o.compress(P, i, 4, to_np32(grads[i]), None, M_ref)
+        assert_indices_match(R.packed[i].cpu().numpy(), ref, L.b, f"worker {i}")
+
+
+@pytest.mark.parametrize("b,g,agg_bits,n", [(4, 30, 8, 8), (4, 30, 8, 1), (4, 30, 8, 3), (4, 30, 16, 16), (2, 8, 8, 16),
+                                            (4, 15, 8, 17), (1, 1, 8, 64), (8, 255, 16, 5), (2, 3, 16, 64), (4, 36, 16, 64)])
+def test_aggregate_bit_exact(b, g, agg_bits, n):
+    d = 5 * 1024
+    T = table_for(b, g) if g > 2 ** b - 1 else list(range(2 ** b))
+    P, L = both_params(d, 1024, n, b=b, g=g, agg_bits=agg_bits, table=T)
+    rng = np.random.default_rng(b * 100 + n)
+    packed = [rng.integers(0, 256, size=d * b // 8, dtype=np.uint8) for _ in range(n)]
+    if n >= 2:
+        packed[0][:] = 0xFF                      # every index at the top: exercises the largest sums
+        packed[1][: d * b // 16] = 0xFF
+    R = GpuRound(L)
+    for i in range(n):
+        R.packed[i].copy_(torch.from_numpy(packed[i]))
+    R.aggregate()
+    ref = o.aggregate(P, packed)
+    assert np.array_equal(R.agg_numpy(), ref)
+
+
+def test_aggregate_all_top_indices_reach_g_times_n():
+    P, L = both_params(4096, 1024, 8)
+    R = GpuRound(L)
+    for t in R.packed:
+        t.fill_(0xFF)
+    R.aggregate()
+    assert np.all(R.agg_numpy() == 240)          # g*n = 240 fits 8 bits (Sec. 8 setup)
+
+
+@pytest.mark.parametrize("block,K,agg_bits,n", [(1 << 10, 3, 8, 4), (1 << 12, 2, 16, 12), (1 << 13, 2, 8, 8), (1 << 16, 2, 8, 2),
+                                                (1 << 20, 1, 8, 8)])
+def test_decompress(block, K, agg_bits, n):
+    d = block * K
+    P, L = both_params(d, block, n, agg_bits=agg_bits)
+    rng = np.random.default_rng(d + n)
+    Y = rng.integers(0, 30 * n + 1, size=d).astype(np.uint8 if agg_bits == 8 else np.uint16)
+    M = (rng.uniform(0.5, 2.0, size=K) * 1e-3).astype(F32)
+    R = GpuRound(L)
+    R.agg.copy_(torch.from_numpy(Y.view(np.uint8)))
+    R.decompress(9, range_M=torch.from_numpy(M).to(DEV))
+    ref = o.decompress(P, 9, Y, M)
+    got = R.out.cpu().numpy()
+    assert rel_l2(got, ref) <= 1e-5
+    assert np.array_equal(got, ref), "fixed butterfly order should make this bit-identical"
+
+
+# ----------------------------------------------------------------------------- whole rounds
+@pytest.mark.parametrize("block,K,n,b,g,agg_bits", [(1 << 10, 9, 4, 4, 30, 8), (1 << 14, 2, 8, 4, 30, 8), (1 << 20, 1, 4, 4, 30, 8),
+                                                    (1 << 12, 3, 16, 2, 8, 8), (1 << 12, 3, 16, 4, 30, 16), (1 << 11, 4, 2, 1, 1, 8),
+                                                    (1 << 13, 2, 3, 8, 255, 16)])
+def test_full_round_on_gpu_ranges(block, K, n, b, g, agg_bits):
+    """prepare_range -> compress x n -> aggregate -> decompress, the GPU using its own range."""
+    d = block * K
+    T = table_for(b, g) if g > 2 ** b - 1 else list(range(2 ** b))
+    P, L = both_params(d, block, n, b=b, g=g, agg_bits=agg_bits, table=T)
+    grads = make_grads(d, n, seed=7 * n + b)
+    R = GpuRound(L)
+    dg = [x.to(DEV) for x in grads]
+    R.prepare(2, dg)
+    R.compress_all(2, dg)
+    R.aggregate()
+    R.decompress(2)
+    M, packed, Y, out, _ = o.thc_round(P, 2, [to_np32(x) for x in grads])
+    M_gpu = R.range_M.cpu().numpy()
+    assert np.all(np.abs(M_gpu - M) <= np.abs(M) * 2.0 ** -23)
+    if np.array_equal(M_gpu, M):                 # identical ranges (the usual case): everything is comparable bit for bit
+        for i in range(n):
+            assert_indices_match(R.packed[i].cpu().numpy(), packed[i], b, f"worker {i}")
+        ag = R.agg_numpy()
+        assert np.mean(ag != Y) <= 1e-6 * n
+        assert rel_l2(R.out.cpu().numpy(), out) <= 1e-5
+    # in any case the estimate must be as good as the oracle's
+    mean = np.mean([to_np32(x).astype(np.float64) for x in grads], axis=0)
+    assert o.nmse(mean, R.out.cpu().numpy()) == pytest.approx(o.nmse(mean, out), rel=0.02)
+
+
+def test_error_feedback_rounds():
+    """Two rounds with error feedback: e' = (grad + e) - RHT^-1(X_i), carried into the next round."""
+    block, K, n = 1 << 12, 3, 3
+    d = block * K
+    P, L = both_params(d, block, n)
+    R = GpuRound(L, ef=True)
+    efs_ref = [np.zeros(d, dtype=F32) for _ in range(n)]
+    for rnd in range(2):
+        grads = make_grads(d, n, seed=40 + rnd)
+        dg = [x.to(DEV) for x in grads]
+        gn = [to_np32(x) for x in grads]
+        M_ref = o.prepare_range(P, gn, efs_ref)
+        R.prepare(rnd, dg)
+        M_gpu = R.range_M.cpu().numpy()
+        assert np.all(np.abs(M_gpu - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
+        R.compress_all(rnd, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+        new_ref = []
+        for i in range(n):
+            pk, ne = o.compress(P, i, rnd, gn[i], efs_ref[i], M_ref)
+            assert_indices_match(R.packed[i].cpu().numpy(), pk, 4, f"round {rnd} worker {i}")
+            got = R.efs[i].cpu().numpy()
+            assert rel_l2(got, ne) <= 1e-5, f"round {rnd} worker {i}"
+            new_ref.append(ne)
+        efs_ref = new_ref
+        for i in range(n):                       # keep both sides on exactly the same state
+            R.efs[i].copy_(torch.from_numpy(efs_ref[i]))
+
+
+def test_bf16_gradients_with_error_feedback():
+    block, K, n = 1 << 13, 2, 2
+    d = block * K
+    P, L = both_params(d, block, n, bf16=True)
+    grads = make_grads(d, n, seed=5, bf16=True)
+    R = GpuRound(L, ef=True)
+    for e in R.efs:
+        e.copy_(torch.randn(d, device=DEV) * 1e-4)
+    efs0 = [e.cpu().numpy() for e in R.efs]
+    dg = [x.to(DEV) for x in grads]
+    gn = [to_np32(x) for x in grads]
+    M_ref = o.prepare_range(P, gn, efs0)
+    R.prepare(1, dg)
+    assert np.all(np.abs(R.range_M.cpu().numpy() - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
+    R.compress_all(1, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+    for i in range(n):
+        pk, ne = o.compress(P, i, 1, gn[i], efs0[i], M_ref)
+        assert_indices_match(R.packed[i].cpu().numpy(), pk, 4)
+        assert rel_l2(R.efs[i].cpu().numpy(), ne) <= 1e-5
+
+
+@pytest.mark.parametrize("L", [21, 23])
+def test_blocks_that_need_a_middle_pass(L):
+    """B > 2^20: bits above the first 13 are split over an in-place middle pass and the final pass."""
+    block, n = 1 << L, 1
+    P, Lp = both_params(block, block, n)
+    grads = make_grads(block, n, seed=L)
+    R = GpuRound(Lp, ef=True)
+    dg = [x.to(DEV) for x in grads]
+    R.prepare(0, dg)
+    gn = [to_np32(x) for x in grads]
+    M_ref = o.prepare_range(P, gn, [np.zeros(block, dtype=F32)])
+    R.compress_all(0, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+    pk, ne = o.compress(P, 0, 0, gn[0], np.zeros(block, dtype=F32), M_ref)
+    assert_indices_match(R.packed[0].cpu().numpy(), pk, 4)
+    assert rel_l2(R.efs[0].cpu().numpy(), ne) <= 1e-5
+    R.aggregate()
+    R.decompress(0, range_M=torch.from_numpy(M_ref).to(DEV))
+    ref = o.decompress(P, 0, o.aggregate(P, [pk]), M_ref)
+    assert rel_l2(R.out.cpu().numpy(), ref) <= 1e-5
+
+
+# ----------------------------------------------------------------------------- degenerate cases
+def test_all_zero_block_and_zero_padding():
+    block, K, n = 1 << 12, 3, 2
+    d = block * K
+    P, L = both_params(d, block, n)
+    grads = make_grads(d, n, seed=3)
+    for x in grads:
+        x[block:2 * block] = 0                   # an all-zero block: M = 0, every index 0, decodes to 0
+        x[2 * block + 100:] = 0                  # a partly padded block
+    R = GpuRound(L)
+    dg = [x.to(DEV) for x in grads]
+    R.prepare(0, dg)
+    R.compress_all(0, dg)
+    R.aggregate()
+    R.decompress(0)
+    M, packed, Y, out, _ = o.thc_round(P, 0, [to_np32(x) for x in grads])
+    assert R.range_M.cpu().numpy()[1] == 0.0 and M[1] == 0.0
+    for i in range(n):
+        pk = R.packed[i].cpu().numpy()
+        assert np.all(pk[block // 2: block] == 0)
+    got = R.out.cpu().numpy()
+    assert np.all(got[block:2 * block] == 0)
+    if np.array_equal(R.range_M.cpu().numpy(), M):
+        for i in range(n):
+            assert_indices_match(R.packed[i].cpu().numpy(), packed[i], 4)
+        assert rel_l2(got, out) <= 1e-5
+
+
+def test_outliers_are_clamped_like_the_oracle():
+    block, n = 1 << 14, 2
+    P, L = both_params(block, block, n)
+    grads = make_grads(block, n, seed=11)
+    grads[0][::997] = 0.5                        # heavy outliers: many rotated coordinates leave [-M, M]
+    R = GpuRound(L)
+    dg = [x.to(DEV) for x in grads]
+    M_ref = o.prepare_range(P, [to_np32(x) for x in grads])
+    R.prepare(6, dg)
+    R.compress_all(6, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+    for i in range(n):
+        ref, _ = o.compress(P, i, 6, to_np32(grads[i]), None, M_ref)
+        assert_indices_match(R.packed[i].cpu().numpy(), ref, 4)
+        z = o.unpack_indices(ref, 4)
+        assert (z == 0).mean() > 0.005 and (z == 15).mean() > 0.005
+
+
+def test_caller_supplied_range_without_the_range_kernel():
+    block, n = 1 << 13, 2
+    P, L = both_params(2 * block, block, n)
+    grads = make_grads(2 * block, n, seed=13)
+    R = GpuRound(L)
+    dg = [x.to(DEV) for x in grads]
+    R.prepare(0, dg, with_range=False)           # only the half-rotated vectors
+    M = np.array([3e-3, 5e-3], dtype=F32)
+    R.compress_all(0, dg, range_M=torch.from_numpy(M).to(DEV))
+    for i in range(n):
+        ref, _ = o.compress(P, i, 0, to_np32(grads[i]), None, M)
+        assert_indices_match(R.packed[i].cpu().numpy(), ref, 4)
+
+
+def test_rounds_and_workers_use_different_random_streams_and_calls_are_deterministic():
+    block, n = 1 << 13, 2
+    P, L = both_params(block, block, n)
+    g = make_grads(block, 1, seed=17)[0]
+    grads = [g, g.clone()]                       # identical gradients on both workers
+    R = GpuRound(L)
+    dg = [x.to(DEV) for x in grads]
+    R.prepare(0, dg)
+    R.compress_all(0, dg)
+    a0, a1 = R.packed[0].cpu().numpy().copy(), R.packed[1].cpu().numpy().copy()
+    assert not np.array_equal(a0, a1)            # independent rounding per worker (App. A)
+    R.prepare(0, dg)
+    R.compress_all(0, dg)
+    assert np.array_equal(R.packed[0].cpu().numpy(), a0)      # same inputs, same bytes
+    R.prepare(1, dg)
+    R.compress_all(1, dg)
+    assert not np.array_equal(R.packed[0].cpu().numpy(), a0)  # D^r and the draws change with the round
+
+
+# ----------------------------------------------------------------------------- the bench configuration
+def test_vgg16_shape_full_size_sampled_blocks():
+    """The 138M-coordinate / 2^28-padded, 8-worker, b=4 configuration in the launch shape bench.py times.
+    The oracle checks sampled blocks one by one (blocks are independent THC instances); properties cover
+    the rest: zero padding decodes to exactly zero and aggregated sums never exceed g*n."""
+    w = wl.C3
+    free, _ = torch.cuda.mem_get_info()
+    if free < 30 * (1 << 30):
+        pytest.skip("needs ~22 GB of device memory")
+    T = o.solve_table(w.b, w.g, w.p)
+    P_blk = o.Params(d=w.block, block=w.block, n=w.n, b=w.b, g=w.g, t_p=o.t_p_of(w.p), seed=SEED, table=T)
+    L = api.make_params(w.d, w.block, w.n, w.b, w.g, o.t_p_of(w.p), SEED, T, w.agg_bits)
+    grads = [wl.gradient(w, i, device=DEV) for i in range(w.n)]
+    R = GpuRound(L)
+    rnd = 5
+    R.prepare(rnd, grads)
+    R.compress_all(rnd, grads)
+    R.aggregate()
+    R.decompress(rnd)
+    torch.cuda.synchronize()
+    M_gpu = R.range_M.cpu().numpy()
+    first_pad = (w.real + w.block - 1) // w.block          # blocks from here on are all zero
+    assert np.all(M_gpu[first_pad:] == 0) and np.all(M_gpu[:first_pad] > 0)
+    assert int(R.agg.max()) <= w.g * w.n
+    assert float(R.out[first_pad * w.block:].abs().max()) == 0.0
+    B = w.block
+    for k in (0, 14, 63, 131, first_pad - 1):              # conv part, FC part, the partly padded block
+        sl = slice(k * B, (k + 1) * B)
+        gn = [g[sl].cpu().numpy() for g in grads]
+        M_ref = o.prepare_range(P_blk, gn)
+        assert abs(M_gpu[k] - M_ref[0]) <= abs(M_ref[0]) * 2.0 ** -23
+        if M_gpu[k] != M_ref[0]:
+            continue
+        packed_ref = []
+        for i in range(w.n):
+            pk, _ = o.compress(P_blk, i, rnd, gn[i], None, M_ref, j0=k * B)
+            assert_indices_match(R.packed[i][k * B // 2:(k + 1) * B // 2].cpu().numpy(), pk, w.b, f"block {k} worker {i}")
+            packed_ref.append(pk)
+        Y = o.aggregate(P_blk, packed_ref)
+        assert np.mean(R.agg[sl].cpu().numpy() != Y) <= 1e-5
+        ref = o.decompress(P_blk, rnd, Y, M_ref, j0=k * B)
+        assert rel_l2(R.out[sl].cpu().numpy(), ref) <= 1e-5
