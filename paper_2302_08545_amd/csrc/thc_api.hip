@@ -2,6 +2,7 @@
 #include "thc.h"
 
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <vector>
 
@@ -71,7 +72,12 @@ size_t ws_x_bytes(const thc_params* p) { return (size_t)p->n * (size_t)p->d * si
 
 uint64_t tiles_of(uint64_t d) { return (d + TILE - 1) / TILE; }
 
-int check_launch() { return hipGetLastError() == hipSuccess ? THC_OK : THC_ELAUNCH; }
+int check_launch() {
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return THC_OK;
+  std::fprintf(stderr, "libthc: kernel launch failed: %s\n", hipGetErrorString(e));
+  return THC_ELAUNCH;
+}
 
 template <template <int> class Launcher, class... A>
 void dispatch_0_7(int r, A&&... args) {
