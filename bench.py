@@ -46,6 +46,8 @@ def main():
     ap.add_argument("--workload", default="c3_vgg16")
     ap.add_argument("--blocks", type=int, default=0, help="use only the first N RHT blocks (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain 1 GiB device-to-device copy five times and exit (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (all n simulated workers live on it); use --gpus 1",
@@ -59,6 +61,14 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     api.lib()                                   # fail loudly if the HIP library is missing
     dev = "cuda:0"
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)                      # reads 2^30 bytes and writes 2^30 bytes per launch
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": 1 << 30, "calibrate_copy_bytes_written": 1 << 30}))
+        return
     w = wl.ALL[args.workload]
     if args.blocks:
         w = wl.shrink(w, args.blocks)
