@@ -19,6 +19,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E
 
+# HBM bytes per launch of the dominant kernel (k_fwd_lo) on the default workload, from two rocprofv3 --pmc
+# runs of this file (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled by what the same counter
+# reads for the plain 1 GiB copy of --calibrate-copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).
+# Summary and commands: profiles/k_fwd_lo_c3_vgg16_hbm_bytes.txt
+MEASURED_TRAFFIC_BYTES = {"c3_vgg16": (4194378.8 * 2.0 + 8397600.4 * 1.0) * 1024.0}
+
 
 def cpu_baseline(w, table, t_p, seed, budget_blocks=8):
     """The oracle as it stands, timed on the host on a bounded sample: the first block(s) of the same
@@ -148,7 +154,8 @@ def main():
         "compulsory_bytes_per_coord": bpc,
         "stage_ms": stage_ms,
         "roofline": {"bound": "hbm", "kernel": "k_fwd_lo (thc_prepare_range)", "achieved": achieved,
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None},
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "algorithmic_bytes": lo_alg_bytes, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, table, t_p, seed)

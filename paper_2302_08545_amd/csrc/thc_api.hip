@@ -97,19 +97,34 @@ template <int R> struct LaunchMid {
   static void run(const MidArgs& a, uint64_t tiles, hipStream_t s) { k_mid<R><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a); }
 };
 template <int R> struct LaunchQuant {
-  static void run(const QuantArgs& a, uint64_t tiles, hipStream_t s) { k_fwd_hi_quant<R><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a); }
+  static void run(const QuantArgs& a, bool cfold, uint64_t tiles, hipStream_t s) {
+    if (cfold && R >= 2) k_fwd_hi_quant<R, true><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a);
+    else k_fwd_hi_quant<R, false><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a);
+  }
 };
 template <int R> struct LaunchInvHi {
   static void run(const InvHiArgs& a, uint64_t tiles, hipStream_t s) { k_inv_hi<R><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a); }
 };
 
-void launch_fwd_lo(int L1, const FwdLoArgs& a, uint64_t tiles, uint32_t n, hipStream_t s) {
-  const dim3 grid((unsigned)tiles, n), blk(NT);
+template <int L1>
+void launch_fwd_lo_t(const FwdLoArgs& a, bool bf16, bool ef, dim3 grid, hipStream_t s) {
+  const dim3 blk(NT);
+  if (bf16) {
+    if (ef) k_fwd_lo<L1, true, true><<<grid, blk, 0, s>>>(a);
+    else k_fwd_lo<L1, true, false><<<grid, blk, 0, s>>>(a);
+  } else {
+    if (ef) k_fwd_lo<L1, false, true><<<grid, blk, 0, s>>>(a);
+    else k_fwd_lo<L1, false, false><<<grid, blk, 0, s>>>(a);
+  }
+}
+
+void launch_fwd_lo(int L1, const FwdLoArgs& a, bool bf16, bool ef, uint64_t tiles, uint32_t n, hipStream_t s) {
+  const dim3 grid((unsigned)tiles, n);
   switch (L1) {
-    case 10: k_fwd_lo<10><<<grid, blk, 0, s>>>(a); break;
-    case 11: k_fwd_lo<11><<<grid, blk, 0, s>>>(a); break;
-    case 12: k_fwd_lo<12><<<grid, blk, 0, s>>>(a); break;
-    default: k_fwd_lo<13><<<grid, blk, 0, s>>>(a); break;
+    case 10: launch_fwd_lo_t<10>(a, bf16, ef, grid, s); break;
+    case 11: launch_fwd_lo_t<11>(a, bf16, ef, grid, s); break;
+    case 12: launch_fwd_lo_t<12>(a, bf16, ef, grid, s); break;
+    default: launch_fwd_lo_t<13>(a, bf16, ef, grid, s); break;
   }
 }
 
@@ -194,9 +209,7 @@ int thc_prepare_range(const thc_params* p, uint64_t round, const void* const* gr
   a.round = (uint32_t)round;
   a.k0 = (uint32_t)p->seed;
   a.k1 = (uint32_t)(p->seed >> 32);
-  a.bf16 = p->in_dtype == THC_DTYPE_BF16;
-  a.has_ef = ef != nullptr;
-  launch_fwd_lo(pl.L1, a, tiles_of(p->d), p->n, s);
+  launch_fwd_lo(pl.L1, a, p->in_dtype == THC_DTYPE_BF16, ef != nullptr, tiles_of(p->d), p->n, s);
   if (range_M) {
     RangeArgs r{a.partials, range_M, p->d, p->n, (uint32_t)pl.L, (uint32_t)pl.L1, p->t_p};
     k_range<<<dim3((unsigned)(p->d / p->block)), dim3(64), 0, s>>>(r);
@@ -241,7 +254,7 @@ int thc_compress(const thc_params* p, uint32_t worker_id, uint64_t round, const 
     const uint32_t wd = z0 < top ? (uint32_t)(p->table[z0 + 1] - lo) : 255u;   // 255: the top value never rounds up
     q.lut[k] = lo | wd << 8 | z0 << 16;
   }
-  dispatch_0_7<LaunchQuant>(pl.R, q, tiles_of(p->d), s);
+  dispatch_0_7<LaunchQuant>(pl.R, q, (pl.L & 1) == 0, tiles_of(p->d), s);
 
   if (ef_inout) {
     InvLoArgs lo{};

@@ -88,8 +88,9 @@ __device__ __forceinline__ void bfly_f4(float4& x) {   // strides 1 and 2 inside
 __device__ __forceinline__ int swz(int i) { return i ^ (((i >> 6) & 7) << 2); }
 
 // One round: every thread gathers 16 values as (16 >> NB) groups of 2^NB values that differ in index
-// bits [P, P+NB), runs the butterflies, and hands each result to sink(index, value).
-template <int P, int NB, class Sink>
+// bits [P, P+NB), runs the butterflies, and hands each result to sink(index, value).  SWZ selects the
+// swizzled layout; rounds with P >= 6 read 64 consecutive values per wave and need none.
+template <int P, int NB, bool SWZ, class Sink>
 __device__ __forceinline__ void lds_round(const float* lds, int t, Sink&& sink) {
   constexpr int E = 1 << NB;
   constexpr int G = 16 >> NB;
@@ -99,7 +100,7 @@ __device__ __forceinline__ void lds_round(const float* lds, int t, Sink&& sink) 
     const int base = (vt & ((1 << P) - 1)) | ((vt >> P) << (P + NB));
     float v[E];
 #pragma unroll
-    for (int e = 0; e < E; ++e) v[e] = lds[swz(base + (e << P))];
+    for (int e = 0; e < E; ++e) v[e] = lds[SWZ ? swz(base + (e << P)) : base + (e << P)];
     bfly<NB>(v);
 #pragma unroll
     for (int e = 0; e < E; ++e) sink(base + (e << P), v[e]);
@@ -108,19 +109,25 @@ __device__ __forceinline__ void lds_round(const float* lds, int t, Sink&& sink) 
 
 // Stages for index bits [P, HI) on a tile resident in LDS.  When FUSE is set the last round hands its
 // results to `sink` (typically a global store) instead of writing them back to LDS.
-template <int P, int HI, bool FUSE, class Sink>
+template <int P, int HI, bool FUSE, bool SWZ, class Sink>
 __device__ __forceinline__ void lds_stages(float* lds, int t, Sink&& sink) {
   constexpr int NB = (HI - P) < 4 ? (HI - P) : 4;
   constexpr bool LAST = (P + NB == HI);
   __syncthreads();
   if constexpr (LAST && FUSE) {
-    lds_round<P, NB>(lds, t, sink);
+    lds_round<P, NB, SWZ>(lds, t, sink);
   } else {
     if constexpr (NB > 0) {
-      lds_round<P, NB>(lds, t, [&](int i, float v) { lds[swz(i)] = v; });
+      lds_round<P, NB, SWZ>(lds, t, [&](int i, float v) { lds[SWZ ? swz(i) : i] = v; });
     }
-    if constexpr (!LAST) lds_stages<P + NB, HI, FUSE>(lds, t, sink);
+    if constexpr (!LAST) lds_stages<P + NB, HI, FUSE, SWZ>(lds, t, sink);
   }
+}
+
+__device__ __forceinline__ void bf4(float4& a, float4& b) {   // (a, b) -> (a + b, a - b), four columns at once
+  const float4 s = make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
+  b = make_float4(a.x - b.x, a.y - b.y, a.z - b.z, a.w - b.w);
+  a = s;
 }
 
 // fixed-order butterfly sum over the 64 lanes of a wave; every lane ends with the same total

@@ -19,16 +19,27 @@ namespace thc {
 // ---------------------------------------------------------------------------------------------
 struct FwdLoArgs {
   PtrArr grads;
-  PtrArr efs;          // unused when !has_ef
+  PtrArr efs;          // unused without error feedback
   float* ws_x;         // n * d floats
   double* partials;    // n * (d >> min(L, 13)) doubles
   uint64_t d;
   uint32_t round, k0, k1;
-  uint32_t bf16, has_ef;
 };
 
-template <int L1>
+template <bool BF16>
+__device__ __forceinline__ float4 load_grad4(const void* g, uint64_t j) {
+  if constexpr (BF16) {
+    const ushort4 h = *reinterpret_cast<const ushort4*>(static_cast<const uint16_t*>(g) + j);
+    return make_float4(bf16_to_f32(h.x), bf16_to_f32(h.y), bf16_to_f32(h.z), bf16_to_f32(h.w));
+  } else {
+    return *reinterpret_cast<const float4*>(static_cast<const float*>(g) + j);
+  }
+}
+
+template <int L1, bool BF16, bool EF>
 __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
+  // Vectors are multiples of B, so only blocks shorter than a tile can leave the last tile partial.
+  constexpr bool GUARD = L1 < LOG_TILE;
   __shared__ __align__(16) float lds[TILE];
   __shared__ uint32_t sgn[TILE / 32];
   __shared__ double wsum[4][NT / 64];
@@ -36,6 +47,22 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
   const int t = threadIdx.x;
   const uint32_t worker = blockIdx.y;
   const uint64_t off = (uint64_t)blockIdx.x * TILE;
+  const void* grad = a.grads.p[worker];
+  const float* ef = EF ? static_cast<const float*>(a.efs.p[worker]) : nullptr;
+
+  // all loads of the tile are issued before anything waits on them
+  float4 x[4], e[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint64_t j = off + 4u * (uint32_t)(i * NT + t);
+    const bool ok = !GUARD || j < a.d;
+    x[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    e[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (ok) {
+      x[i] = load_grad4<BF16>(grad, j);
+      if constexpr (EF) e[i] = *reinterpret_cast<const float4*>(ef + j);
+    }
+  }
 
   if (t < 64) {   // the tile's 8192 diagonal entries: 64 Philox calls of 128 bits
     const uint64_t q = (off >> 7) + t;
@@ -43,25 +70,10 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
     *reinterpret_cast<uint4*>(&sgn[4 * t]) = r;
   }
 
-  float4 x[4];
+  if constexpr (EF) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint64_t j = off + 4u * (uint32_t)(i * NT + t);
-    x[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (j < a.d) {
-      if (a.bf16) {
-        const ushort4 h = *reinterpret_cast<const ushort4*>(static_cast<const uint16_t*>(a.grads.p[worker]) + j);
-        x[i] = make_float4(bf16_to_f32(h.x), bf16_to_f32(h.y), bf16_to_f32(h.z), bf16_to_f32(h.w));
-      } else {
-        x[i] = *reinterpret_cast<const float4*>(static_cast<const float*>(a.grads.p[worker]) + j);
-      }
-      if (a.has_ef) {
-        const float4 e = *reinterpret_cast<const float4*>(static_cast<const float*>(a.efs.p[worker]) + j);
-        x[i].x += e.x; x[i].y += e.y; x[i].z += e.z; x[i].w += e.w;
-      }
-    }
+    for (int i = 0; i < 4; ++i) { x[i].x += e[i].x; x[i].y += e[i].y; x[i].z += e[i].z; x[i].w += e[i].w; }
   }
-  __syncthreads();
 
   // sum of squares in binary64 (a binary32 square is exact there)
   double acc[4];
@@ -85,6 +97,7 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
       if (lane == 0) wsum[i][wave] = s;
     }
   }
+  __syncthreads();   // diagonal bits visible
 
   // diagonal, strides 1 and 2, then into LDS
 #pragma unroll
@@ -101,12 +114,11 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
 
   float* dst = a.ws_x + (uint64_t)worker * a.d + off;
   const uint64_t left = a.d - off;   // coordinates of this tile that exist (tail tile of a short vector)
-  lds_stages<2, L1, true>(lds, t, [&](int i, float v) {
-    if ((uint64_t)i < left) dst[i] = v;
+  lds_stages<2, L1, true, true>(lds, t, [&](int i, float v) {
+    if (!GUARD || (uint64_t)i < left) dst[i] = v;
   });
 
-  // partial sums: one per block of 2^L1 coordinates inside the tile, combined in a fixed order.
-  // (the __syncthreads inside lds_stages made wsum visible)
+  // partial sums: one per block of 2^L1 coordinates inside the tile, combined in a fixed order
   constexpr int NBLK = TILE >> L1;
   if (t < NBLK) {
     double s = 0.0;
@@ -175,16 +187,83 @@ struct HiGeom {
   }
 };
 
+// Front half of a strided pass with R >= 2 row bits (no bounds checks: such tiles are always whole).
+// Each thread loads four rows (4 rho + 0..3) of four consecutive columns, finishes row bits 0 and 1 in
+// registers, parks the tile in LDS (row-major, no padding) and runs row bits [2, 2 + NB1) as one LDS
+// round.  What is left is NB2 = R - 2 - NB1 (0 or 1) top bits for the caller's epilogue.
+template <int R>
+struct HiSplit {
+  static constexpr int LOGW = LOG_TILE - R;
+  static constexpr int W = 1 << LOGW;
+  static constexpr int NB1 = (R - 2) < 4 ? (R - 2) : 4;
+  static constexpr int NB2 = R - 2 - NB1;
+  static_assert(R >= 2 && R <= 7 && NB2 <= 1, "strided pass handles 2..7 row bits");
+};
+
+template <int R>
+__device__ __forceinline__ void hi_front(const float* src, const HiGeom<R>& g, float* lds, int t) {
+  using S = HiSplit<R>;
+  const int cg = t & (S::W / 4 - 1), rho = t >> (S::LOGW - 2);
+  const float* p = src + g.base + ((uint64_t)(4 * rho) << g.s0) + 4 * cg;
+  const uint64_t pitch = 1ull << g.s0;
+  float4 x0 = *reinterpret_cast<const float4*>(p);
+  float4 x1 = *reinterpret_cast<const float4*>(p + pitch);
+  float4 x2 = *reinterpret_cast<const float4*>(p + 2 * pitch);
+  float4 x3 = *reinterpret_cast<const float4*>(p + 3 * pitch);
+  bf4(x0, x1); bf4(x2, x3);   // row bit 0
+  bf4(x0, x2); bf4(x1, x3);   // row bit 1
+  float* q = lds + (4 * rho) * S::W + 4 * cg;
+  *reinterpret_cast<float4*>(q) = x0;
+  *reinterpret_cast<float4*>(q + S::W) = x1;
+  *reinterpret_cast<float4*>(q + 2 * S::W) = x2;
+  *reinterpret_cast<float4*>(q + 3 * S::W) = x3;
+  // row bits [2, 2 + NB1)  <->  tile index bits [LOGW + 2, LOGW + 2 + NB1)
+  lds_stages<S::LOGW + 2, S::LOGW + 2 + S::NB1, false, false>(lds, t, [](int, float) {});
+  __syncthreads();
+}
+
+// Two groups of eight consecutive coordinates per thread, with the last row bit (if any) applied:
+// tile index of each group in idx[], values in v[][].
+template <int R>
+__device__ __forceinline__ void hi_back(const float* lds, int t, int (&idx)[2], float (&v)[2][8]) {
+  using S = HiSplit<R>;
+  if constexpr (S::NB2 == 1) {
+    const int oct = t & (S::W / 8 - 1), r = t >> (S::LOGW - 3);      // r < 2^(R-1)
+    idx[0] = r * S::W + 8 * oct;
+    idx[1] = idx[0] + (TILE >> 1);
+  } else {
+    idx[0] = 8 * t;
+    idx[1] = 8 * (t + NT);
+  }
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const float4 p0 = *reinterpret_cast<const float4*>(&lds[idx[h]]);
+    const float4 p1 = *reinterpret_cast<const float4*>(&lds[idx[h] + 4]);
+    v[h][0] = p0.x; v[h][1] = p0.y; v[h][2] = p0.z; v[h][3] = p0.w;
+    v[h][4] = p1.x; v[h][5] = p1.y; v[h][6] = p1.z; v[h][7] = p1.w;
+  }
+  if constexpr (S::NB2 == 1) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float a = v[0][e], b = v[1][e];
+      v[0][e] = a + b;
+      v[1][e] = a - b;
+    }
+  }
+}
+
+// generic (slow) front for R < 2 and partial tiles: whole transform part through LDS
 template <int R>
 __device__ __forceinline__ void hi_load_to_lds(const float* src, const HiGeom<R>& g, uint64_t d, float* lds, int t) {
+  float4 v[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int idx = 4 * (i * NT + t);
-    const uint64_t j = g.coord(idx);
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (j < d) v = *reinterpret_cast<const float4*>(src + j);
-    *reinterpret_cast<float4*>(&lds[swz(idx)]) = v;
+    const uint64_t j = g.coord(4 * (i * NT + t));
+    v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (j < d) v[i] = *reinterpret_cast<const float4*>(src + j);
   }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) *reinterpret_cast<float4*>(&lds[4 * (i * NT + t)]) = v[i];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -201,14 +280,27 @@ __global__ __launch_bounds__(NT) void k_mid(const MidArgs a) {
   __shared__ __align__(16) float lds[TILE];
   const int t = threadIdx.x;
   const HiGeom<R> g(blockIdx.x, a.s0);
-  hi_load_to_lds<R>(a.x, g, a.d, lds, t);
-  lds_stages<LOG_TILE - R, LOG_TILE, false>(lds, t, [](int, float) {});
-  __syncthreads();
+  if constexpr (R >= 2) {
+    hi_front<R>(a.x, g, lds, t);
+    int idx[2];
+    float v[2][8];
+    hi_back<R>(lds, t, idx, v);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int idx = 4 * (i * NT + t);
-    const uint64_t j = g.coord(idx);
-    if (j < a.d) *reinterpret_cast<float4*>(a.x + j) = *reinterpret_cast<const float4*>(&lds[swz(idx)]);
+    for (int h = 0; h < 2; ++h) {
+      float* o = a.x + g.coord(idx[h]);
+      *reinterpret_cast<float4*>(o) = make_float4(v[h][0], v[h][1], v[h][2], v[h][3]);
+      *reinterpret_cast<float4*>(o + 4) = make_float4(v[h][4], v[h][5], v[h][6], v[h][7]);
+    }
+  } else {
+    hi_load_to_lds<R>(a.x, g, a.d, lds, t);
+    lds_stages<LOG_TILE - R, LOG_TILE, false, false>(lds, t, [](int, float) {});
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int idx = 4 * (i * NT + t);
+      const uint64_t j = g.coord(idx);
+      if (j < a.d) *reinterpret_cast<float4*>(a.x + j) = *reinterpret_cast<const float4*>(&lds[idx]);
+    }
   }
 }
 
@@ -219,7 +311,9 @@ __global__ __launch_bounds__(NT) void k_mid(const MidArgs a) {
 // Per coordinate, in binary32:  v = h * c;  x' = med(v, -M, M);  y16 = (x' + M) * (scale * 2^16);
 // k = floor(y16 / 2^16);  (lo, wd, z0) = LUT[k];  t16 = y16 - lo * 2^16;
 // up iff (half + 1/2) * wd < t16  (one fused multiply-add, then compare);  z = z0 + up.
-// The top table entry carries wd = 255 so that it can never round up.
+// The top table entry carries wd = 255 so that it can never round up.  When 1/sqrt(B) is a power of
+// two (even log2 B) the multiplication by c is folded into M and the scale: that only moves exponents,
+// so every rounding stays where it was.
 // ---------------------------------------------------------------------------------------------
 struct QuantArgs {
   const float* x;          // one worker's half-rotated vector, d floats
@@ -234,76 +328,123 @@ struct QuantArgs {
   uint32_t lut[256];       // per grid cell k: lo | wd << 8 | z0 << 16
 };
 
-template <int R>
+struct QuantScalars {
+  float M, negM, sc16, c;  // for even log2 B: M and sc16 are pre-divided / pre-multiplied by c, and c is unused
+};
+
+template <bool CFOLD>
+__device__ __forceinline__ void quantize8(const float (&hv)[8], const uint4 rnd, const QuantScalars s,
+                                          const uint2* lut, uint32_t (&z)[8]) {
+  const uint32_t rw[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float v = CFOLD ? hv[e] : hv[e] * s.c;
+    const float xc = __builtin_amdgcn_fmed3f(v, s.negM, s.M);
+    const float y16 = (xc + s.M) * s.sc16;
+    const uint32_t ki = (uint32_t)y16;
+    const uint2 ent = lut[(ki >> 16) & 255u];
+    const float t16 = y16 - __uint_as_float(ent.x);
+    const float wd = (float)(ent.y & 255u);
+    const float hf = (float)((e & 1) ? (rw[e >> 1] >> 16) : (rw[e >> 1] & 0xFFFFu));
+    const float prod = __builtin_fmaf(hf, wd, 0.5f * wd);
+    z[e] = (ent.y >> 8) + (prod < t16 ? 1u : 0u);
+  }
+}
+
+__device__ __forceinline__ void store_packed8(uint8_t* packed, uint64_t j, uint32_t b, const uint32_t (&z)[8]) {
+  if (b == 4) {
+    uint32_t w = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) w |= z[e] << (4 * e);
+    *reinterpret_cast<uint32_t*>(packed + (j >> 1)) = w;
+  } else if (b == 2) {
+    uint32_t w = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) w |= z[e] << (2 * e);
+    *reinterpret_cast<uint16_t*>(packed + (j >> 2)) = (uint16_t)w;
+  } else if (b == 8) {
+    const uint32_t w0 = z[0] | z[1] << 8 | z[2] << 16 | z[3] << 24;
+    const uint32_t w1 = z[4] | z[5] << 8 | z[6] << 16 | z[7] << 24;
+    *reinterpret_cast<uint2*>(packed + j) = make_uint2(w0, w1);
+  } else {
+    uint32_t w = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) w |= z[e] << e;
+    packed[j >> 3] = (uint8_t)w;
+  }
+}
+
+__device__ __forceinline__ void build_quant_lut(const QuantArgs& a, uint2* lut, int t) {
+  if (t < 256) {
+    const uint32_t ent = a.lut[t];
+    lut[t] = make_uint2(__float_as_uint((float)(ent & 255u) * 65536.0f), ent >> 8);
+  }
+}
+
+__device__ __forceinline__ float scale16_of(float M, uint32_t g) {
+  return M > 0.f ? (float)((double)g / (2.0 * (double)M)) * 65536.0f : 0.f;
+}
+
+template <int R, bool CFOLD>
 __global__ __launch_bounds__(NT) void k_fwd_hi_quant(const QuantArgs a) {
   __shared__ __align__(16) float lds[TILE];
-  __shared__ uint32_t lut[256];
+  __shared__ uint2 lut[256];
   __shared__ float sM[8], sScale[8];
 
   const int t = threadIdx.x;
   const HiGeom<R> g(blockIdx.x, a.s0);
+  build_quant_lut(a, lut, t);
 
-  if (t < 256) lut[t] = a.lut[t];
-  // per-block scalars; a tile spans more than one block only when B < 8192 (then R == 0)
-  const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
-  if (t < nblk) {
-    const uint64_t blk = (g.base >> a.L) + t;
-    float M = 0.f;
-    if (blk < (a.d >> a.L)) M = a.range_M[blk];
-    sM[t] = M;
-    sScale[t] = M > 0.f ? (float)((double)a.g / (2.0 * (double)M)) * 65536.0f : 0.f;
-  }
-
-  hi_load_to_lds<R>(a.x, g, a.d, lds, t);
-  lds_stages<LOG_TILE - R, LOG_TILE, false>(lds, t, [](int, float) {});
-  __syncthreads();
-
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int idx = 8 * (t + NT * h);
-    const uint64_t j = g.coord(idx);
-    if (j >= a.d) continue;
-    const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
-    const float M = sM[bt], sc = sScale[bt], negM = -M;
-    const float4 p0 = *reinterpret_cast<const float4*>(&lds[swz(idx)]);
-    const float4 p1 = *reinterpret_cast<const float4*>(&lds[swz(idx + 4)]);
-    const float hv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-    const uint64_t q = j >> 3;
-    const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, a.worker, a.k0, a.k1);
-    const uint32_t rw[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
-    uint32_t z[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float v = hv[e] * a.c;
-      const float xc = __builtin_fminf(__builtin_fmaxf(v, negM), M);
-      const float y16 = (xc + M) * sc;
-      const uint32_t ki = (uint32_t)y16;
-      const uint32_t ent = lut[(ki >> 16) & 255u];
-      const float lo = (float)(ent & 255u), wd = (float)((ent >> 8) & 255u);
-      const float t16 = __builtin_fmaf(lo, -65536.0f, y16);
-      const float hf = (float)((e & 1) ? (rw[e >> 1] >> 16) : (rw[e >> 1] & 0xFFFFu));
-      const float prod = __builtin_fmaf(hf, wd, 0.5f * wd);
-      z[e] = (ent >> 16) + (prod < t16 ? 1u : 0u);
+  if constexpr (R >= 2) {
+    // the whole tile lies in one block
+    if (t == 0) {
+      const float M = a.range_M[g.base >> a.L];
+      const float sc = scale16_of(M, a.g);
+      sM[0] = CFOLD ? M * (1.0f / a.c) : M;
+      sScale[0] = CFOLD ? sc * a.c : sc;
     }
-    if (a.b == 4) {
-      uint32_t w = 0;
+    hi_front<R>(a.x, g, lds, t);
+    int idx[2];
+    float v[2][8];
+    hi_back<R>(lds, t, idx, v);
+    const QuantScalars s{sM[0], -sM[0], sScale[0], a.c};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) w |= z[e] << (4 * e);
-      *reinterpret_cast<uint32_t*>(a.packed + (j >> 1)) = w;
-    } else if (a.b == 2) {
-      uint32_t w = 0;
+    for (int h = 0; h < 2; ++h) {
+      const uint64_t j = g.coord(idx[h]);
+      const uint64_t q = j >> 3;
+      const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, a.worker, a.k0, a.k1);
+      uint32_t z[8];
+      quantize8<CFOLD>(v[h], rnd, s, lut, z);
+      store_packed8(a.packed, j, a.b, z);
+    }
+  } else {
+    // per-block scalars; a tile spans more than one block only when B < 8192 (then R == 0)
+    const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
+    if (t < nblk) {
+      const uint64_t blk = (g.base >> a.L) + t;
+      float M = 0.f;
+      if (blk < (a.d >> a.L)) M = a.range_M[blk];
+      sM[t] = M;
+      sScale[t] = scale16_of(M, a.g);
+    }
+    hi_load_to_lds<R>(a.x, g, a.d, lds, t);
+    lds_stages<LOG_TILE - R, LOG_TILE, false, false>(lds, t, [](int, float) {});
+    __syncthreads();
 #pragma unroll
-      for (int e = 0; e < 8; ++e) w |= z[e] << (2 * e);
-      *reinterpret_cast<uint16_t*>(a.packed + (j >> 2)) = (uint16_t)w;
-    } else if (a.b == 8) {
-      const uint32_t w0 = z[0] | z[1] << 8 | z[2] << 16 | z[3] << 24;
-      const uint32_t w1 = z[4] | z[5] << 8 | z[6] << 16 | z[7] << 24;
-      *reinterpret_cast<uint2*>(a.packed + j) = make_uint2(w0, w1);
-    } else {
-      uint32_t w = 0;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) w |= z[e] << e;
-      a.packed[j >> 3] = (uint8_t)w;
+    for (int h = 0; h < 2; ++h) {
+      const int idx = 8 * (t + NT * h);
+      const uint64_t j = g.coord(idx);
+      if (j >= a.d) continue;
+      const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
+      const QuantScalars s{sM[bt], -sM[bt], sScale[bt], a.c};
+      const float4 p0 = *reinterpret_cast<const float4*>(&lds[idx]);
+      const float4 p1 = *reinterpret_cast<const float4*>(&lds[idx + 4]);
+      const float hv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+      const uint64_t q = j >> 3;
+      const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, a.worker, a.k0, a.k1);
+      uint32_t z[8];
+      quantize8<false>(hv, rnd, s, lut, z);
+      store_packed8(a.packed, j, a.b, z);
     }
   }
 }
@@ -327,12 +468,38 @@ struct InvLoArgs {
 
 template <int L1>
 __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
+  constexpr bool GUARD = L1 < LOG_TILE;
   __shared__ __align__(16) float lds[TILE];
   __shared__ float sM[8], sStep[8];
   __shared__ float tabf[256];
 
   const int t = threadIdx.x;
   const uint64_t off = (uint64_t)blockIdx.x * TILE;
+  const int idx = 16 * t;
+  const uint64_t j = off + idx;
+  const bool ok = !GUARD || j < a.d;
+
+  // raw bits first, so the load is in flight while the block constants are prepared
+  uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  const uint8_t* s8 = static_cast<const uint8_t*>(a.src);
+  if (ok) {
+    if (a.src_bits == 8) {
+      const uint4 r = *reinterpret_cast<const uint4*>(s8 + j);
+      w[0] = r.x; w[1] = r.y; w[2] = r.z; w[3] = r.w;
+    } else if (a.src_bits == 16) {
+      const uint4 r0 = *reinterpret_cast<const uint4*>(s8 + 2 * j);
+      const uint4 r1 = *reinterpret_cast<const uint4*>(s8 + 2 * j + 16);
+      w[0] = r0.x; w[1] = r0.y; w[2] = r0.z; w[3] = r0.w; w[4] = r1.x; w[5] = r1.y; w[6] = r1.z; w[7] = r1.w;
+    } else if (a.src_bits == 4) {
+      const uint2 r = *reinterpret_cast<const uint2*>(s8 + (j >> 1));
+      w[0] = r.x; w[1] = r.y;
+    } else if (a.src_bits == 2) {
+      w[0] = *reinterpret_cast<const uint32_t*>(s8 + (j >> 2));
+    } else {
+      w[0] = *reinterpret_cast<const uint16_t*>(s8 + (j >> 3));
+    }
+  }
+
   const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
   if (t < nblk) {
     const uint64_t blk = (off >> a.L) + t;
@@ -344,46 +511,30 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
   if (a.use_table && t < 256) tabf[t] = (float)a.table[t];
   __syncthreads();
 
-  const int idx = 16 * t;
-  const uint64_t j = off + idx;
+  uint32_t y[16];
+  if (a.src_bits == 8) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 2] >> (8 * (e & 3))) & 255u;
+  } else if (a.src_bits == 16) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+  } else if (a.src_bits == 4) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 3] >> (4 * (e & 7))) & 15u;
+  } else if (a.src_bits == 2) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[0] >> (2 * e)) & 3u;
+  } else {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[0] >> e) & 1u;
+  }
+  const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
+  const float negM = -sM[bt], step = sStep[bt];
   float v[16];
 #pragma unroll
-  for (int e = 0; e < 16; ++e) v[e] = 0.f;
-  if (j < a.d) {
-    uint32_t y[16];
-    const uint8_t* s8 = static_cast<const uint8_t*>(a.src);
-    if (a.src_bits == 8) {
-      const uint4 r = *reinterpret_cast<const uint4*>(s8 + j);
-      const uint32_t w[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-      for (int e = 0; e < 16; ++e) y[e] = (w[e >> 2] >> (8 * (e & 3))) & 255u;
-    } else if (a.src_bits == 16) {
-      const uint4 r0 = *reinterpret_cast<const uint4*>(s8 + 2 * j);
-      const uint4 r1 = *reinterpret_cast<const uint4*>(s8 + 2 * j + 16);
-      const uint32_t w[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
-#pragma unroll
-      for (int e = 0; e < 16; ++e) y[e] = (w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-    } else if (a.src_bits == 4) {
-      const uint2 r = *reinterpret_cast<const uint2*>(s8 + (j >> 1));
-      const uint32_t w[2] = {r.x, r.y};
-#pragma unroll
-      for (int e = 0; e < 16; ++e) y[e] = (w[e >> 3] >> (4 * (e & 7))) & 15u;
-    } else if (a.src_bits == 2) {
-      const uint32_t w = *reinterpret_cast<const uint32_t*>(s8 + (j >> 2));
-#pragma unroll
-      for (int e = 0; e < 16; ++e) y[e] = (w >> (2 * e)) & 3u;
-    } else {
-      const uint32_t w = *reinterpret_cast<const uint16_t*>(s8 + (j >> 3));
-#pragma unroll
-      for (int e = 0; e < 16; ++e) y[e] = (w >> e) & 1u;
-    }
-    const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
-    const float negM = -sM[bt], step = sStep[bt];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const float f = a.use_table ? tabf[y[e]] : (float)y[e];
-      v[e] = f * step + negM;
-    }
+  for (int e = 0; e < 16; ++e) {
+    const float f = a.use_table ? tabf[y[e]] : (float)y[e];
+    v[e] = ok ? f * step + negM : 0.f;
   }
   bfly<4>(v);
 #pragma unroll
@@ -392,8 +543,8 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
 
   float* dst = a.ws_x + off;
   const uint64_t left = a.d - off;
-  lds_stages<4, L1, true>(lds, t, [&](int i, float val) {
-    if ((uint64_t)i < left) dst[i] = val;
+  lds_stages<4, L1, true, true>(lds, t, [&](int i, float val) {
+    if (!GUARD || (uint64_t)i < left) dst[i] = val;
   });
 }
 
@@ -413,6 +564,20 @@ struct InvHiArgs {
   float c;
 };
 
+__device__ __forceinline__ float4 inv_finish4(float4 v, uint32_t bits, const InvHiArgs& a, uint64_t j) {
+  v.x = flip(v.x * a.c, bits & 1u);
+  v.y = flip(v.y * a.c, (bits >> 1) & 1u);
+  v.z = flip(v.z * a.c, (bits >> 2) & 1u);
+  v.w = flip(v.w * a.c, (bits >> 3) & 1u);
+  if (a.mode == 1) {
+    float4 x = a.bf16 ? load_grad4<true>(a.grad, j) : load_grad4<false>(a.grad, j);
+    const float4 e = *reinterpret_cast<const float4*>(a.out + j);
+    x.x += e.x; x.y += e.y; x.z += e.z; x.w += e.w;
+    v = make_float4(x.x - v.x, x.y - v.y, x.z - v.z, x.w - v.w);
+  }
+  return v;
+}
+
 template <int R>
 __global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
   __shared__ __align__(16) float lds[TILE];
@@ -421,36 +586,37 @@ __global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
   const int t = threadIdx.x;
   const HiGeom<R> g(blockIdx.x, a.s0);
 
-  if (t < TILE / 32) sgn[t] = sign_word(g.coord(32 * t), a.round, a.k0, a.k1);
-
-  hi_load_to_lds<R>(a.x, g, a.d, lds, t);
-  lds_stages<LOG_TILE - R, LOG_TILE, false>(lds, t, [](int, float) {});
-  __syncthreads();
-
+  if constexpr (R >= 2) {
+    hi_front<R>(a.x, g, lds, t);
+    // 32 consecutive tile indices are 32 consecutive coordinates (rows are at least 64 wide)
+    if (t < TILE / 32) sgn[t] = sign_word(g.coord(32 * t), a.round, a.k0, a.k1);
+    int idx[2];
+    float v[2][8];
+    hi_back<R>(lds, t, idx, v);
+    __syncthreads();
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int idx = 4 * (i * NT + t);
-    const uint64_t j = g.coord(idx);
-    if (j >= a.d) continue;
-    float4 v = *reinterpret_cast<const float4*>(&lds[swz(idx)]);
-    const uint32_t bits = sgn[idx >> 5] >> (idx & 31);
-    v.x = flip(v.x * a.c, bits & 1u);
-    v.y = flip(v.y * a.c, (bits >> 1) & 1u);
-    v.z = flip(v.z * a.c, (bits >> 2) & 1u);
-    v.w = flip(v.w * a.c, (bits >> 3) & 1u);
-    if (a.mode == 1) {
-      float4 x;
-      if (a.bf16) {
-        const ushort4 h = *reinterpret_cast<const ushort4*>(static_cast<const uint16_t*>(a.grad) + j);
-        x = make_float4(bf16_to_f32(h.x), bf16_to_f32(h.y), bf16_to_f32(h.z), bf16_to_f32(h.w));
-      } else {
-        x = *reinterpret_cast<const float4*>(static_cast<const float*>(a.grad) + j);
-      }
-      const float4 e = *reinterpret_cast<const float4*>(a.out + j);
-      x.x += e.x; x.y += e.y; x.z += e.z; x.w += e.w;
-      v = make_float4(x.x - v.x, x.y - v.y, x.z - v.z, x.w - v.w);
+    for (int h = 0; h < 2; ++h) {
+      const uint64_t j = g.coord(idx[h]);
+      const uint32_t bits = sgn[idx[h] >> 5] >> (idx[h] & 31);
+      const float4 o0 = inv_finish4(make_float4(v[h][0], v[h][1], v[h][2], v[h][3]), bits, a, j);
+      const float4 o1 = inv_finish4(make_float4(v[h][4], v[h][5], v[h][6], v[h][7]), bits >> 4, a, j + 4);
+      *reinterpret_cast<float4*>(a.out + j) = o0;
+      *reinterpret_cast<float4*>(a.out + j + 4) = o1;
     }
-    *reinterpret_cast<float4*>(a.out + j) = v;
+  } else {
+    if (t < TILE / 32) sgn[t] = sign_word(g.coord(32 * t), a.round, a.k0, a.k1);
+    hi_load_to_lds<R>(a.x, g, a.d, lds, t);
+    lds_stages<LOG_TILE - R, LOG_TILE, false, false>(lds, t, [](int, float) {});
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int idx = 4 * (i * NT + t);
+      const uint64_t j = g.coord(idx);
+      if (j >= a.d) continue;
+      const float4 v = *reinterpret_cast<const float4*>(&lds[idx]);
+      const uint32_t bits = sgn[idx >> 5] >> (idx & 31);
+      *reinterpret_cast<float4*>(a.out + j) = inv_finish4(v, bits, a, j);
+    }
   }
 }
 
