@@ -106,25 +106,29 @@ template <int R> struct LaunchInvHi {
   static void run(const InvHiArgs& a, uint64_t tiles, hipStream_t s) { k_inv_hi<R><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a); }
 };
 
+template <int L1, bool BF16, bool EF>
+void launch_fwd_lo_k(const FwdLoArgs& a, uint64_t tiles, uint32_t n, hipStream_t s) {
+  const dim3 grid((unsigned)tiles, n);
+  k_fwd_lo<L1, BF16, EF><<<grid, dim3(NT), 0, s>>>(a);
+}
+
 template <int L1>
-void launch_fwd_lo_t(const FwdLoArgs& a, bool bf16, bool ef, dim3 grid, hipStream_t s) {
-  const dim3 blk(NT);
+void launch_fwd_lo_t(const FwdLoArgs& a, bool bf16, bool ef, uint64_t tiles, uint32_t n, hipStream_t s) {
   if (bf16) {
-    if (ef) k_fwd_lo<L1, true, true><<<grid, blk, 0, s>>>(a);
-    else k_fwd_lo<L1, true, false><<<grid, blk, 0, s>>>(a);
+    if (ef) launch_fwd_lo_k<L1, true, true>(a, tiles, n, s);
+    else launch_fwd_lo_k<L1, true, false>(a, tiles, n, s);
   } else {
-    if (ef) k_fwd_lo<L1, false, true><<<grid, blk, 0, s>>>(a);
-    else k_fwd_lo<L1, false, false><<<grid, blk, 0, s>>>(a);
+    if (ef) launch_fwd_lo_k<L1, false, true>(a, tiles, n, s);
+    else launch_fwd_lo_k<L1, false, false>(a, tiles, n, s);
   }
 }
 
 void launch_fwd_lo(int L1, const FwdLoArgs& a, bool bf16, bool ef, uint64_t tiles, uint32_t n, hipStream_t s) {
-  const dim3 grid((unsigned)tiles, n);
   switch (L1) {
-    case 10: launch_fwd_lo_t<10>(a, bf16, ef, grid, s); break;
-    case 11: launch_fwd_lo_t<11>(a, bf16, ef, grid, s); break;
-    case 12: launch_fwd_lo_t<12>(a, bf16, ef, grid, s); break;
-    default: launch_fwd_lo_t<13>(a, bf16, ef, grid, s); break;
+    case 10: launch_fwd_lo_t<10>(a, bf16, ef, tiles, n, s); break;
+    case 11: launch_fwd_lo_t<11>(a, bf16, ef, tiles, n, s); break;
+    case 12: launch_fwd_lo_t<12>(a, bf16, ef, tiles, n, s); break;
+    default: launch_fwd_lo_t<13>(a, bf16, ef, tiles, n, s); break;
   }
 }
 

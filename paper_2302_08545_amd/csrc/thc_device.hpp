@@ -81,26 +81,42 @@ __device__ __forceinline__ void bfly_f4(float4& x) {   // strides 1 and 2 inside
 }
 
 // ---------------------------------------------------------------------------------------------
-// LDS tile of TILE floats.  Logical index -> physical slot: bits 2..4 are XORed with bits 6..8 so that
-// the strided gathers of every round hit 32 distinct banks per half-wave; bits 0..1 are untouched, so a
-// group of four consecutive, 4-aligned values stays a 16-byte unit.
+// LDS tile of TILE floats, three layouts (logical index -> physical slot):
+//   PLAIN  identity.  Enough when every round reads 64 consecutive values per wave (P >= 6).
+//   SWZ    bits 2..4 ^= bits 6..8: strided gathers of any round hit 32 distinct banks per half-wave.
+//   PAD    four unused floats after every 64: the same property, and the 16 values a thread gathers in a
+//          round sit at a constant physical stride, so their addresses are immediate offsets.
+// All three keep four consecutive, 4-aligned values together as one 16-byte unit.
 // ---------------------------------------------------------------------------------------------
+enum Layout { PLAIN = 0, SWZ = 1, PAD = 2 };
+constexpr int TILE_PAD = TILE + 4 * (TILE / 64);
+
 __device__ __forceinline__ int swz(int i) { return i ^ (((i >> 6) & 7) << 2); }
 
+template <Layout LY>
+__device__ __forceinline__ int phys(int i) {
+  if constexpr (LY == SWZ) return swz(i);
+  else if constexpr (LY == PAD) return i + 4 * (i >> 6);
+  else return i;
+}
+
 // One round: every thread gathers 16 values as (16 >> NB) groups of 2^NB values that differ in index
-// bits [P, P+NB), runs the butterflies, and hands each result to sink(index, value).  SWZ selects the
-// swizzled layout; rounds with P >= 6 read 64 consecutive values per wave and need none.
-template <int P, int NB, bool SWZ, class Sink>
+// bits [P, P+NB), runs the butterflies, and hands each result to sink(index, value).
+template <int P, int NB, Layout LY, class Sink>
 __device__ __forceinline__ void lds_round(const float* lds, int t, Sink&& sink) {
   constexpr int E = 1 << NB;
   constexpr int G = 16 >> NB;
+  // physical distance between consecutive gathered values (PLAIN / PAD only)
+  constexpr int ESTR = (LY == PAD && P >= 6) ? (1 << P) + 4 * (1 << (P - 6)) : (1 << P);
+  static_assert(LY != PAD || P >= 6 || P + NB <= 6, "a padded gather must not straddle a 64-value group");
 #pragma unroll
   for (int gi = 0; gi < G; ++gi) {
     const int vt = t + NT * gi;
     const int base = (vt & ((1 << P) - 1)) | ((vt >> P) << (P + NB));
+    const float* pb = lds + phys<LY>(base);
     float v[E];
 #pragma unroll
-    for (int e = 0; e < E; ++e) v[e] = lds[SWZ ? swz(base + (e << P)) : base + (e << P)];
+    for (int e = 0; e < E; ++e) v[e] = (LY == SWZ) ? lds[swz(base + (e << P))] : pb[e * ESTR];
     bfly<NB>(v);
 #pragma unroll
     for (int e = 0; e < E; ++e) sink(base + (e << P), v[e]);
@@ -109,18 +125,18 @@ __device__ __forceinline__ void lds_round(const float* lds, int t, Sink&& sink) 
 
 // Stages for index bits [P, HI) on a tile resident in LDS.  When FUSE is set the last round hands its
 // results to `sink` (typically a global store) instead of writing them back to LDS.
-template <int P, int HI, bool FUSE, bool SWZ, class Sink>
+template <int P, int HI, bool FUSE, Layout LY, class Sink>
 __device__ __forceinline__ void lds_stages(float* lds, int t, Sink&& sink) {
   constexpr int NB = (HI - P) < 4 ? (HI - P) : 4;
   constexpr bool LAST = (P + NB == HI);
   __syncthreads();
   if constexpr (LAST && FUSE) {
-    lds_round<P, NB, SWZ>(lds, t, sink);
+    lds_round<P, NB, LY>(lds, t, sink);
   } else {
     if constexpr (NB > 0) {
-      lds_round<P, NB, SWZ>(lds, t, [&](int i, float v) { lds[SWZ ? swz(i) : i] = v; });
+      lds_round<P, NB, LY>(lds, t, [&](int i, float v) { lds[phys<LY>(i)] = v; });
     }
-    if constexpr (!LAST) lds_stages<P + NB, HI, FUSE, SWZ>(lds, t, sink);
+    if constexpr (!LAST) lds_stages<P + NB, HI, FUSE, LY>(lds, t, sink);
   }
 }
 
