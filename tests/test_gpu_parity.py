@@ -400,3 +400,62 @@ def test_vgg16_shape_full_size_sampled_blocks():
         assert np.mean(R.agg[sl].cpu().numpy() != Y) <= 1e-5
         ref = o.decompress(P_blk, rnd, Y, M_ref, j0=k * B)
         assert rel_l2(R.out[sl].cpu().numpy(), ref) <= 1e-5
+
+
+# ----------------------------------------------------------------------------- the other workload recipes
+def _round_vs_oracle(w, rnd=1, rounds=1):
+    """Whole rounds of a (shrunk) workload on the GPU against the oracle; the oracle's range is injected."""
+    T = o.solve_table(w.b, w.g, w.p)
+    tp = o.t_p_of(w.p)
+    P = o.Params(d=w.d, block=w.block, n=w.n, b=w.b, g=w.g, t_p=tp, seed=SEED, table=T, agg_bits=w.agg_bits)
+    L = api.make_params(w.d, w.block, w.n, w.b, w.g, tp, SEED, T, w.agg_bits,
+                        api.THC_DTYPE_BF16 if w.dtype == "bf16" else api.THC_DTYPE_F32)
+    grads = [wl.gradient(w, i, device=DEV) for i in range(w.n)]
+    gn = [to_np32(g) for g in grads]
+    R = GpuRound(L, ef=w.ef)
+    efs_ref = [np.zeros(w.d, dtype=F32) for _ in range(w.n)] if w.ef else None
+    for r in range(rnd, rnd + rounds):
+        M_ref = o.prepare_range(P, gn, efs_ref)
+        R.prepare(r, grads)
+        M_gpu = R.range_M.cpu().numpy()
+        assert np.all(np.abs(M_gpu - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
+        dM = torch.from_numpy(M_ref).to(DEV)
+        R.compress_all(r, grads, range_M=dM)
+        packed_ref, new_efs = [], []
+        for i in range(w.n):
+            pk, ne = o.compress(P, i, r, gn[i], None if efs_ref is None else efs_ref[i], M_ref)
+            assert_indices_match(R.packed[i].cpu().numpy(), pk, w.b, f"{w.name} round {r} worker {i}")
+            packed_ref.append(pk)
+            if w.ef:
+                assert rel_l2(R.efs[i].cpu().numpy(), ne) <= 1e-5
+                new_efs.append(ne)
+        R.aggregate()
+        Y = o.aggregate(P, packed_ref)
+        assert np.mean(R.agg_numpy() != Y) <= 1e-6 * w.n
+        R.decompress(r, range_M=dM)
+        assert rel_l2(R.out.cpu().numpy(), o.decompress(P, r, Y, M_ref)) <= 1e-5
+        if w.ef:
+            efs_ref = new_efs
+            for i in range(w.n):
+                R.efs[i].copy_(torch.from_numpy(efs_ref[i]))
+
+
+def test_workload_c1_full():
+    _round_vs_oracle(wl.C1)                                  # d = 2^20, n = 4: the whole configuration
+
+
+def test_workload_c2_shape_single_transform_with_error_feedback():
+    # ResNet-50 shape: one 2^25-point transform over the zero-padded vector, Laplace segments, error feedback,
+    # two rounds so that the second one reads a real error buffer.  Two of the eight workers.
+    _round_vs_oracle(wl.shrink(wl.C2, 1, n=2), rnd=0, rounds=2)
+
+
+@pytest.mark.parametrize("w", [wl.C4_B4, wl.C4_B2], ids=lambda w: w.name)
+def test_workload_c4_shape_first_blocks(w):
+    # BERT-large shape: 16 workers with different sigmas and 50-sigma outliers; b = 4 -> 16-bit sums, b = 2 -> 8-bit
+    _round_vs_oracle(wl.shrink(w, 2))
+
+
+def test_workload_c5_shape_first_block():
+    # GPT-2-XL shape: bf16 gradients, Student-t tails, 2^22 blocks, error feedback; 3 of the 32 workers
+    _round_vs_oracle(wl.shrink(wl.C5, 1, n=3), rnd=0, rounds=2)
