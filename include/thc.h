@@ -26,8 +26,9 @@
  *   - Vector layout: a worker's gradient is one flat vector of d coordinates (padded by the caller with
  *     zeros to a multiple of `block`).  The RHT, the norm and the range are per block of `block`
  *     consecutive coordinates (the paper's 4 MB partition is block = 2^20).
- *   - Packed index stream: coordinate j occupies bits [(j*b) mod 8, +b) of byte (j*b) div 8.
- *   - Aggregated stream: one little-endian unsigned integer of agg_bits per coordinate.
+ *   - Packed index stream and aggregated stream: bit streams of b-bit (agg_bits-bit) fields, field j at
+ *     stream bits [j*w, j*w + w), stream bit k being bit (k mod 8) of byte (k div 8).  For agg_bits 8 / 16
+ *     that is an array of little-endian uint8 / uint16.
  *   - Random numbers: Philox4x32-10 keyed by `seed`.  Rademacher diagonal D^r: coordinate j takes bit
  *     (j mod 32) of word ((j div 32) mod 4) of Philox(counter (q, q>>32, round, 0x80000000)), q = j div 128.
  *     Rounding draw of worker i: coordinate j takes 16-bit half (j mod 8) (low half first) of
@@ -62,9 +63,9 @@ typedef struct thc_params {
   uint64_t d;          /* padded coordinate count per worker; a multiple of `block`                        */
   uint64_t block;      /* B: RHT block, a power of two, 2^10 <= B <= 2^27, B divides d                     */
   uint32_t n;          /* number of workers, 1 <= n <= THC_MAX_WORKERS                                     */
-  uint32_t b;          /* bits per table index: 1, 2, 4 or 8                                               */
+  uint32_t b;          /* bits per table index, 1..8 (1, 2, 4, 8 have fast paths)                          */
   uint32_t g;          /* granularity: 2^b - 1 <= g <= 255 (Sec. 4.3)                                      */
-  uint32_t agg_bits;   /* width of an aggregated value: 8 or 16; g*n < 2^agg_bits                          */
+  uint32_t agg_bits;   /* width of an aggregated value, 1..16 (8 and 16 have fast paths); g*n < 2^agg_bits */
   uint32_t in_dtype;   /* THC_DTYPE_F32 or THC_DTYPE_BF16 (widened to binary32 inside the kernel)          */
   float    t_p;        /* truncation threshold Phi^-1(1 - p/2) (Sec. 5.1); see thc_threshold               */
   uint64_t seed;       /* shared by all workers and the decompressor                                       */

@@ -172,6 +172,7 @@ class Params:
         assert T[0] == 0 and T[-1] == self.g and all(T[i] < T[i + 1] for i in range(len(T) - 1)), \
             "homomorphism precondition of Sec. 4.3: 0 = T[0] < ... < T[2^b-1] = g"
         assert self.block & (self.block - 1) == 0 and self.d % self.block == 0
+        assert 1 <= self.b <= 8 and 1 <= self.agg_bits <= 16
         assert self.g * self.n < 2 ** self.agg_bits, "aggregated sums must fit (Sec. 8 setup: g*n <= 255 at 8 bits)"
         self.table = T
         # F[k] = largest index z with T[z] <= k, for every grid cell k in 0..g
@@ -266,25 +267,30 @@ def prepare_range(P: Params, grads: Sequence[np.ndarray],
 
 
 # --------------------------------------------------------------------------- #
-# Bit packing: coordinate j lives in byte (j*b) div 8 at bit offset (j*b) mod 8,
-# least-significant bits first (paper silent; b in {1, 2, 4, 8}).
+# Bit packing (paper silent): a stream of w-bit fields, field j occupying bits [j*w, j*w + w) of the
+# stream, the stream's bit k being bit (k mod 8) of byte (k div 8) -- least-significant bits first.
+# Used for the index stream (w = b) and for the aggregated stream (w = agg_bits).
 # --------------------------------------------------------------------------- #
+def pack_fields(values: np.ndarray, w: int) -> np.ndarray:
+    assert 1 <= w <= 16
+    v = np.asarray(values, dtype=np.uint32)
+    assert (v.size * w) % 8 == 0 and int(v.max(initial=0)) < (1 << w)
+    bits = ((v[:, None] >> np.arange(w, dtype=np.uint32)[None, :]) & 1).astype(np.uint8)   # field-major, LSB first
+    return np.packbits(bits.reshape(-1), bitorder="little")
+
+
+def unpack_fields(packed: np.ndarray, w: int) -> np.ndarray:
+    assert 1 <= w <= 16
+    bits = np.unpackbits(np.asarray(packed, dtype=np.uint8), bitorder="little").reshape(-1, w).astype(np.uint32)
+    return (bits << np.arange(w, dtype=np.uint32)[None, :]).sum(axis=1).astype(np.uint32)
+
+
 def pack_indices(z: np.ndarray, b: int) -> np.ndarray:
-    assert b in (1, 2, 4, 8)
-    per = 8 // b
-    z = np.asarray(z, dtype=np.uint8).reshape(-1, per)
-    out = np.zeros(z.shape[0], dtype=np.uint8)
-    for s in range(per):
-        out |= (z[:, s] << np.uint8(s * b)).astype(np.uint8)
-    return out
+    return pack_fields(z, b)
 
 
 def unpack_indices(packed: np.ndarray, b: int) -> np.ndarray:
-    assert b in (1, 2, 4, 8)
-    per = 8 // b
-    p = np.asarray(packed, dtype=np.uint8)
-    cols = [(p >> np.uint8(s * b)) & np.uint8((1 << b) - 1) for s in range(per)]
-    return np.stack(cols, axis=1).reshape(-1)
+    return unpack_fields(packed, b).astype(np.uint8)
 
 
 # --------------------------------------------------------------------------- #
@@ -368,13 +374,19 @@ def compress(P: Params, worker: int, rnd: int, grad: np.ndarray, ef: Optional[np
 # Main stage, PS side (Alg. 2: Y = sum_i T[Z_i]) and worker-side decompression
 # --------------------------------------------------------------------------- #
 def aggregate(P: Params, packed: Sequence[np.ndarray]) -> np.ndarray:
-    """Y[j] = sum over workers of T[Z_i[j]], exact integers, stored at agg_bits per coordinate."""
+    """Y[j] = sum over workers of T[Z_i[j]], exact integers (uint8 if they fit a byte, else uint16)."""
     T = np.array(P.table, dtype=np.int64)
     Y = np.zeros(P.d, dtype=np.int64)
     for pk in packed:
         Y += T[unpack_indices(pk, P.b).astype(np.int64)]
     assert Y.max(initial=0) < 2 ** P.agg_bits
-    return Y.astype(np.uint8 if P.agg_bits == 8 else np.uint16)
+    return Y.astype(np.uint8 if P.agg_bits <= 8 else np.uint16)
+
+
+def aggregate_stream(P: Params, Y: np.ndarray) -> np.ndarray:
+    """The aggregated sums as the byte stream a PS would send: agg_bits per coordinate (Sec. 8.4 notes that
+    ceil(log2(g n + 1)) bits suffice)."""
+    return pack_fields(Y, P.agg_bits)
 
 
 def decompress(P: Params, rnd: int, Y: np.ndarray, range_M: np.ndarray, j0: int = 0) -> np.ndarray:

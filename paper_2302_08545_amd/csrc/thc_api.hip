@@ -26,9 +26,9 @@ int validate(const thc_params* p) {
   if (p->d == 0 || p->d % p->block) return THC_EINVAL;
   if (p->n < 1) return THC_EINVAL;
   if (p->n > THC_MAX_WORKERS) return THC_EUNSUPPORTED;
-  if (p->b != 1 && p->b != 2 && p->b != 4 && p->b != 8) return THC_EINVAL;
+  if (p->b < 1 || p->b > 8) return THC_EINVAL;
   if (p->g < (1u << p->b) - 1 || p->g > 255) return THC_EINVAL;
-  if (p->agg_bits != 8 && p->agg_bits != 16) return THC_EINVAL;
+  if (p->agg_bits < 1 || p->agg_bits > 16) return THC_EINVAL;
   if (p->in_dtype != THC_DTYPE_F32 && p->in_dtype != THC_DTYPE_BF16) return THC_EINVAL;
   if (!(p->t_p > 0.f) || !std::isfinite(p->t_p)) return THC_EINVAL;
   const uint32_t top = (1u << p->b) - 1;

@@ -153,6 +153,46 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Bit streams of w-bit fields (w <= 16), least-significant bits first: eight consecutive fields occupy
+// exactly w consecutive bytes.  Generic (byte-wise) codec for the widths without a dedicated fast path.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void store_fields8(uint8_t* dst, const uint32_t (&z)[8], uint32_t w) {
+  uint64_t lo = 0, hi = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const uint32_t pos = w * e;
+    if (pos < 64) {
+      lo |= (uint64_t)z[e] << pos;
+      if (pos + w > 64) hi |= (uint64_t)z[e] >> (64 - pos);
+    } else {
+      hi |= (uint64_t)z[e] << (pos - 64);
+    }
+  }
+  for (uint32_t i = 0; i < w; ++i) dst[i] = (uint8_t)(i < 8 ? lo >> (8 * i) : hi >> (8 * (i - 8)));
+}
+
+__device__ __forceinline__ void load_fields8(const uint8_t* src, uint32_t w, uint32_t (&z)[8]) {
+  uint64_t lo = 0, hi = 0;
+  for (uint32_t i = 0; i < w; ++i) {
+    const uint64_t byte = src[i];
+    if (i < 8) lo |= byte << (8 * i); else hi |= byte << (8 * (i - 8));
+  }
+  const uint32_t mask = (1u << w) - 1u;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const uint32_t pos = w * e;
+    uint64_t v;
+    if (pos < 64) {
+      v = lo >> pos;
+      if (pos + w > 64) v |= hi << (64 - pos);
+    } else {
+      v = hi >> (pos - 64);
+    }
+    z[e] = (uint32_t)v & mask;
+  }
+}
+
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
 }  // namespace thc

@@ -396,11 +396,13 @@ __device__ __forceinline__ void store_packed8(uint8_t* packed, uint64_t j, uint3
     const uint32_t w0 = z[0] | z[1] << 8 | z[2] << 16 | z[3] << 24;
     const uint32_t w1 = z[4] | z[5] << 8 | z[6] << 16 | z[7] << 24;
     *reinterpret_cast<uint2*>(packed + j) = make_uint2(w0, w1);
-  } else {
+  } else if (b == 1) {
     uint32_t w = 0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) w |= z[e] << e;
     packed[j >> 3] = (uint8_t)w;
+  } else {
+    store_fields8(packed + (j >> 3) * b, z, b);
   }
 }
 
@@ -515,7 +517,9 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
 
   // raw bits first, so the load is in flight while the block constants are prepared
   uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  uint32_t y[16];
   const uint8_t* s8 = static_cast<const uint8_t*>(a.src);
+  const bool fast = a.src_bits == 8 || a.src_bits == 16 || a.src_bits == 4 || a.src_bits == 2 || a.src_bits == 1;
   if (ok) {
     if (a.src_bits == 8) {
       const uint4 r = *reinterpret_cast<const uint4*>(s8 + j);
@@ -529,8 +533,14 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
       w[0] = r.x; w[1] = r.y;
     } else if (a.src_bits == 2) {
       w[0] = *reinterpret_cast<const uint32_t*>(s8 + (j >> 2));
-    } else {
+    } else if (a.src_bits == 1) {
       w[0] = *reinterpret_cast<const uint16_t*>(s8 + (j >> 3));
+    } else {   // any other width: eight fields take src_bits bytes
+      uint32_t z0[8], z1[8];
+      load_fields8(s8 + (j >> 3) * a.src_bits, a.src_bits, z0);
+      load_fields8(s8 + ((j >> 3) + 1) * a.src_bits, a.src_bits, z1);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { y[e] = z0[e]; y[8 + e] = z1[e]; }
     }
   }
 
@@ -545,7 +555,6 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
   if (a.use_table && t < 256) tabf[t] = (float)a.table[t];
   __syncthreads();
 
-  uint32_t y[16];
   if (a.src_bits == 8) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) y[e] = (w[e >> 2] >> (8 * (e & 3))) & 255u;
@@ -558,10 +567,14 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
   } else if (a.src_bits == 2) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) y[e] = (w[0] >> (2 * e)) & 3u;
-  } else {
+  } else if (a.src_bits == 1) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) y[e] = (w[0] >> e) & 1u;
+  } else if (!ok) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = 0;
   }
+  (void)fast;
   const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
   const float negM = -sM[bt], step = sStep[bt];
   float v[16];
@@ -691,24 +704,37 @@ __global__ __launch_bounds__(256) void k_aggregate_generic(const AggArgs a) {
       const uint32_t w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[e] += tab[(w[e >> 2] >> (8 * (e & 3))) & 255u];
-    } else {
+    } else if (a.b == 1) {
       const uint32_t w = *reinterpret_cast<const uint16_t*>(s8 + (j >> 3));
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[e] += tab[(w >> e) & 1u];
+    } else {
+      uint32_t z0[8], z1[8];
+      load_fields8(s8 + (j >> 3) * a.b, a.b, z0);
+      load_fields8(s8 + ((j >> 3) + 1) * a.b, a.b, z1);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { acc[e] += tab[z0[e]]; acc[8 + e] += tab[z1[e]]; }
     }
   }
+  uint8_t* out = static_cast<uint8_t*>(a.out);
   if (a.agg_bits == 8) {
     uint32_t w[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) w[k] = acc[4 * k] | acc[4 * k + 1] << 8 | acc[4 * k + 2] << 16 | acc[4 * k + 3] << 24;
-    *reinterpret_cast<uint4*>(static_cast<uint8_t*>(a.out) + j) = make_uint4(w[0], w[1], w[2], w[3]);
-  } else {
+    *reinterpret_cast<uint4*>(out + j) = make_uint4(w[0], w[1], w[2], w[3]);
+  } else if (a.agg_bits == 16) {
     uint32_t w[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) w[k] = acc[2 * k] | acc[2 * k + 1] << 16;
-    uint4* o = reinterpret_cast<uint4*>(static_cast<uint8_t*>(a.out) + 2 * j);
+    uint4* o = reinterpret_cast<uint4*>(out + 2 * j);
     o[0] = make_uint4(w[0], w[1], w[2], w[3]);
     o[1] = make_uint4(w[4], w[5], w[6], w[7]);
+  } else {   // exact-width sums (Sec. 8.4: ceil(log2(g n + 1)) bits are enough)
+    uint32_t z0[8], z1[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { z0[e] = acc[e]; z1[e] = acc[8 + e]; }
+    store_fields8(out + (j >> 3) * a.agg_bits, z0, a.agg_bits);
+    store_fields8(out + ((j >> 3) + 1) * a.agg_bits, z1, a.agg_bits);
   }
 }
 

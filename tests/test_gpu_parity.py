@@ -89,7 +89,11 @@ class GpuRound:
 
     def agg_numpy(self):
         a = self.agg.cpu().numpy()
-        return a if self.L.agg_bits == 8 else a.view(np.uint16)
+        if self.L.agg_bits == 8:
+            return a
+        if self.L.agg_bits == 16:
+            return a.view(np.uint16)
+        return o.unpack_fields(a, self.L.agg_bits)
 
 
 def make_grads(d, n, scale=1e-3, seed=1, bf16=False):
@@ -130,7 +134,9 @@ def test_prepare_range_and_compress(block, K, n):
 
 
 @pytest.mark.parametrize("b,g,agg_bits,n", [(4, 30, 8, 8), (4, 30, 8, 1), (4, 30, 8, 3), (4, 30, 16, 16), (2, 8, 8, 16),
-                                            (4, 15, 8, 17), (1, 1, 8, 64), (8, 255, 16, 5), (2, 3, 16, 64), (4, 36, 16, 64)])
+                                            (4, 15, 8, 17), (1, 1, 8, 64), (8, 255, 16, 5), (2, 3, 16, 64), (4, 36, 16, 64),
+                                            (3, 12, 8, 10), (3, 7, 6, 9), (4, 30, 7, 4), (4, 30, 9, 16), (5, 40, 11, 33),
+                                            (2, 8, 7, 15), (6, 63, 13, 64), (7, 200, 16, 9), (1, 1, 1, 1), (4, 30, 5, 1)])
 def test_aggregate_bit_exact(b, g, agg_bits, n):
     d = 5 * 1024
     T = table_for(b, g) if g > 2 ** b - 1 else list(range(2 ** b))
@@ -146,6 +152,7 @@ def test_aggregate_bit_exact(b, g, agg_bits, n):
     R.aggregate()
     ref = o.aggregate(P, packed)
     assert np.array_equal(R.agg_numpy(), ref)
+    assert np.array_equal(R.agg.cpu().numpy(), o.aggregate_stream(P, ref))     # the bytes a PS would send
 
 
 def test_aggregate_all_top_indices_reach_g_times_n():
@@ -158,15 +165,15 @@ def test_aggregate_all_top_indices_reach_g_times_n():
 
 
 @pytest.mark.parametrize("block,K,agg_bits,n", [(1 << 10, 3, 8, 4), (1 << 12, 2, 16, 12), (1 << 13, 2, 8, 8), (1 << 16, 2, 8, 2),
-                                                (1 << 20, 1, 8, 8)])
+                                                (1 << 20, 1, 8, 8), (1 << 11, 3, 7, 4), (1 << 13, 2, 9, 16), (1 << 14, 1, 12, 40)])
 def test_decompress(block, K, agg_bits, n):
     d = block * K
     P, L = both_params(d, block, n, agg_bits=agg_bits)
     rng = np.random.default_rng(d + n)
-    Y = rng.integers(0, 30 * n + 1, size=d).astype(np.uint8 if agg_bits == 8 else np.uint16)
+    Y = rng.integers(0, 30 * n + 1, size=d).astype(np.uint8 if agg_bits <= 8 else np.uint16)
     M = (rng.uniform(0.5, 2.0, size=K) * 1e-3).astype(F32)
     R = GpuRound(L)
-    R.agg.copy_(torch.from_numpy(Y.view(np.uint8)))
+    R.agg.copy_(torch.from_numpy(o.aggregate_stream(P, Y)))
     R.decompress(9, range_M=torch.from_numpy(M).to(DEV))
     ref = o.decompress(P, 9, Y, M)
     got = R.out.cpu().numpy()
@@ -177,7 +184,8 @@ def test_decompress(block, K, agg_bits, n):
 # ----------------------------------------------------------------------------- whole rounds
 @pytest.mark.parametrize("block,K,n,b,g,agg_bits", [(1 << 10, 9, 4, 4, 30, 8), (1 << 14, 2, 8, 4, 30, 8), (1 << 20, 1, 4, 4, 30, 8),
                                                     (1 << 12, 3, 16, 2, 8, 8), (1 << 12, 3, 16, 4, 30, 16), (1 << 11, 4, 2, 1, 1, 8),
-                                                    (1 << 13, 2, 3, 8, 255, 16)])
+                                                    (1 << 13, 2, 3, 8, 255, 16), (1 << 14, 2, 10, 3, 12, 7), (1 << 10, 5, 16, 4, 30, 9),
+                                                    (1 << 15, 1, 5, 6, 100, 10), (1 << 12, 2, 4, 3, 7, 5)])
 def test_full_round_on_gpu_ranges(block, K, n, b, g, agg_bits):
     """prepare_range -> compress x n -> aggregate -> decompress, the GPU using its own range."""
     d = block * K

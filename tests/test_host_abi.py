@@ -54,9 +54,12 @@ def test_workspace_size():
     (dict(d=(1 << 12) + 1), -1),               # not a multiple of the block
     (dict(n=0), -1),
     (dict(n=65, agg_bits=16), -4),             # more workers than a launch can take
-    (dict(b=3), -1),
+    (dict(b=0), -1),
+    (dict(b=9), -1),
     (dict(g=14), -1),                          # g < 2^b - 1
-    (dict(agg_bits=12), -1),
+    (dict(agg_bits=0), -1),
+    (dict(agg_bits=17), -1),
+    (dict(agg_bits=6), -3),                    # 30 * 4 = 120 needs 7 bits
     (dict(t_p=0.0), -1),
     (dict(table=[0, 3, 5, 7, 9, 11, 13, 13, 15, 17, 19, 21, 23, 25, 27, 30]), -2),   # not strictly increasing
     (dict(table=[1] + T430[1:]), -2),          # T[0] != 0

@@ -339,6 +339,25 @@ def test_pack_round_trip_every_value_at_every_position(b):
             assert np.array_equal(o.unpack_indices(pk, b), z)
 
 
+@pytest.mark.parametrize("w", list(range(1, 17)))
+def test_pack_fields_any_width(w):
+    # field j sits at stream bit j*w, least-significant bit first: check against Python big integers
+    rng = np.random.default_rng(w)
+    v = rng.integers(0, 1 << w, size=64, dtype=np.uint32)
+    v[0], v[1] = (1 << w) - 1, 0
+    big = 0
+    for j, x in enumerate(v.tolist()):
+        big |= x << (j * w)
+    expect = np.frombuffer(big.to_bytes(64 * w // 8, "little"), dtype=np.uint8)
+    pk = o.pack_fields(v, w)
+    assert np.array_equal(pk, expect)
+    assert np.array_equal(o.unpack_fields(pk, w), v)
+    if w == 8:
+        assert np.array_equal(pk, v.astype(np.uint8))
+    if w == 16:
+        assert np.array_equal(pk, v.astype("<u2").view(np.uint8))
+
+
 # ------------------------------------------------------------------ lookup / aggregate / homomorphism
 def test_paper_worked_table_examples(golden_dir):
     text = open(os.path.join(golden_dir, "paper_sec4_3_tables.txt")).read()
