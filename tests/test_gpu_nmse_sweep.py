@@ -1,0 +1,69 @@
+"""The NMSE-versus-granularity experiment (App. C.4) on the GPU library: equality with the oracle on a small
+case, and the trends the paper describes (the figure's values themselves are not printed in the paper)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import thc_oracle as o
+from paper_2302_08545_amd import api, nmse_sweep
+
+pytestmark = pytest.mark.gpu
+
+
+def test_sweep_point_equals_oracle():
+    # one (b, g) point at small size, three repeats: the GPU round is bit-identical to the oracle's, so the NMSE is too
+    b, g, n, p, log2d, reps, seed = 3, 12, 3, 1 / 1024, 14, 3, 77
+    rows = nmse_sweep.sweep(bs=(b,), g_max=g, n=n, p=p, log2d=log2d, repeats=reps, seed=seed)
+    row = [r for r in rows if r["g"] == g][0]
+    d = 1 << log2d
+    T = o.solve_table(b, g, p)
+    assert row["table"] == T
+    P = o.Params(d=d, block=d, n=n, b=b, g=g, t_p=o.t_p_of(p), seed=seed, table=T,
+                 agg_bits=math.ceil(math.log2(g * n + 1)))
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(seed + 1000 * b + g)
+    acc = 0.0
+    for r in range(reps):
+        x = torch.randn(d, generator=gen, device="cuda:0", dtype=torch.float32).exp_().cpu().numpy()
+        _, _, _, out, _ = o.thc_round(P, r, [x] * n)
+        acc += o.nmse(x, out)
+    assert row["nmse"] == pytest.approx(acc / reps, rel=1e-6)
+
+
+def test_sweep_trends():
+    rows = nmse_sweep.sweep(bs=(2, 3, 4), g_max=24, n=10, p=1 / 1024, log2d=16, repeats=8)
+    by = {(r["b"], r["g"]): r for r in rows}
+    # measured NMSE follows the Gaussian prediction (table cost / n + truncation term)
+    for r in rows:
+        assert r["nmse"] == pytest.approx(r["predicted"], rel=0.2), r
+    # each extra bit buys close to an order of magnitude (App. C.4)
+    assert by[(2, 20)]["nmse"] > 3.5 * by[(3, 20)]["nmse"] > 3.5 * 3.5 * by[(4, 20)]["nmse"]
+    # finer granularity helps, mildly and not monotonically (a grid that is a multiple of a good coarse grid
+    # contains it): the uniform grid g = 2^b - 1 is never the best choice, and doubling g never hurts
+    for b in (2, 3, 4):
+        g0 = 2 ** b - 1
+        assert min(by[(b, g)]["table_cost"] for g in range(g0 + 1, 25)) < by[(b, g0)]["table_cost"]
+        assert min(by[(b, g)]["nmse"] for g in range(g0 + 1, 25)) < by[(b, g0)]["nmse"]
+        for g in range(g0, 13):
+            assert by[(b, 2 * g)]["table_cost"] <= by[(b, g)]["table_cost"] * (1 + 1e-12)
+
+
+def test_b3_error_feedback_round():
+    # three-bit indices through the error-feedback path (generic field codec in the inverse pass)
+    from tests.test_gpu_parity import GpuRound, both_params, make_grads, assert_indices_match, rel_l2, to_np32, DEV
+    d, block, n = 1 << 13, 1 << 12, 2
+    P, L = both_params(d, block, n, b=3, g=12, agg_bits=5)
+    grads = make_grads(d, n, seed=99)
+    R = GpuRound(L, ef=True)
+    dg = [x.to(DEV) for x in grads]
+    gn = [to_np32(x) for x in grads]
+    efs0 = [np.zeros(d, dtype=np.float32) for _ in range(n)]
+    M_ref = o.prepare_range(P, gn, efs0)
+    R.prepare(0, dg)
+    R.compress_all(0, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+    for i in range(n):
+        pk, ne = o.compress(P, i, 0, gn[i], efs0[i], M_ref)
+        assert_indices_match(R.packed[i].cpu().numpy(), pk, 3)
+        assert rel_l2(R.efs[i].cpu().numpy(), ne) <= 1e-5
