@@ -296,25 +296,33 @@ def unpack_indices(packed: np.ndarray, b: int) -> np.ndarray:
 # --------------------------------------------------------------------------- #
 # Main stage, worker side (Alg. 3: clamp, SQ, Y, Z) and error feedback
 # --------------------------------------------------------------------------- #
-def block_scalars(P: Params, range_M: np.ndarray):
-    """Per-block constants derived from M, each a binary64 quotient rounded once:
-    scale = g/(2M) (0 when M = 0: an all-zero block maps every coordinate to index 0),
-    step_g = 2M/g,  step_n = 2M/(g n)."""
+def block_scalars(P: Params, range_M: np.ndarray, range_m: Optional[np.ndarray] = None):
+    """Per-block constants derived from the range [m, M] (m = -M unless given), each a binary64 quotient
+    rounded once, with the width M - m taken in binary64:
+    scale = g/(M-m) (0 when the width is 0: such a block maps every coordinate to index 0),
+    step_g = (M-m)/g,  step_n = (M-m)/(g n)."""
     M64 = range_M.astype(np.float64)
+    m64 = -M64 if range_m is None else range_m.astype(np.float64)
+    W64 = M64 - m64
     with np.errstate(divide="ignore", invalid="ignore"):
-        scale = np.where(M64 > 0, np.float64(P.g) / (2.0 * M64), 0.0).astype(F32)
-    step_g = ((2.0 * M64) / np.float64(P.g)).astype(F32)
-    step_n = ((2.0 * M64) / np.float64(P.g * P.n)).astype(F32)
+        scale = np.where(W64 > 0, np.float64(P.g) / W64, 0.0).astype(F32)
+    step_g = (W64 / np.float64(P.g)).astype(F32)
+    step_n = (W64 / np.float64(P.g * P.n)).astype(F32)
     return scale, step_g, step_n
 
 
-def quantize_rotated(P: Params, R: np.ndarray, range_M: np.ndarray, h16: np.ndarray) -> np.ndarray:
+def _lower(range_M: np.ndarray, range_m: Optional[np.ndarray]) -> np.ndarray:
+    return (-range_M.astype(F32)) if range_m is None else range_m.astype(F32)
+
+
+def quantize_rotated(P: Params, R: np.ndarray, range_M: np.ndarray, h16: np.ndarray,
+                     range_m: Optional[np.ndarray] = None) -> np.ndarray:
     """Clamp + stochastic quantization onto the table's values + inverse table lookup.
 
-    R: rotated coordinates (float32, length d); h16: the 16-bit random integers.
+    R: (rotated) coordinates (float32, length d); h16: the 16-bit random integers.
     Per coordinate, all in binary32:
-        x' = min(max(R, -M), M)                      truncation (Alg. 3)
-        y  = (x' + M) * scale          in [0, g]     position on the (g+1)-point grid
+        x' = min(max(R, m), M)                       truncation (Alg. 3)
+        y  = (x' - m) * scale          in [0, g]     position on the (g+1)-point grid
         k  = min(floor(y), g);  z0 = F[k]            largest index whose table value is <= y
         top index: stays.  Otherwise lo = T[z0], wd = T[z0+1] - lo, t = y - lo and the
         value goes up to z0+1 exactly when u * wd < t, with u = (h16 + 1/2) / 2^16.
@@ -322,11 +330,12 @@ def quantize_rotated(P: Params, R: np.ndarray, range_M: np.ndarray, h16: np.ndar
     Returns indices z in <2^b> (Alg. 2's Z = T^-1[Y]).
     """
     B = P.block
-    scale, _, _ = block_scalars(P, range_M)
+    scale, _, _ = block_scalars(P, range_M, range_m)
     M = np.repeat(range_M.astype(F32), B)
+    m = np.repeat(_lower(range_M, range_m), B)
     sc = np.repeat(scale, B)
-    xc = np.minimum(np.maximum(R.astype(F32), -M), M)
-    y = ((xc + M).astype(F32) * sc).astype(F32)
+    xc = np.minimum(np.maximum(R.astype(F32), m), M)
+    y = ((xc - m).astype(F32) * sc).astype(F32)
     k = np.minimum(np.floor(y).astype(np.int64), P.g)
     z0 = P.F[k]
     T = np.array(list(P.table) + [P.table[-1]], dtype=np.int64)   # sentinel for the top index
@@ -338,13 +347,14 @@ def quantize_rotated(P: Params, R: np.ndarray, range_M: np.ndarray, h16: np.ndar
     return (z0 + up.astype(np.int64)).astype(np.uint8)
 
 
-def dequantize_indices(P: Params, z: np.ndarray, range_M: np.ndarray) -> np.ndarray:
-    """X = m + T[z] (M - m)/g  (Sec. 4.3, Alg. 2), binary32: float(T[z]) * step_g, then + (-M)."""
-    _, step_g, _ = block_scalars(P, range_M)
+def dequantize_indices(P: Params, z: np.ndarray, range_M: np.ndarray,
+                       range_m: Optional[np.ndarray] = None) -> np.ndarray:
+    """X = m + T[z] (M - m)/g  (Sec. 4.3, Alg. 2), binary32: float(T[z]) * step_g, then + m."""
+    _, step_g, _ = block_scalars(P, range_M, range_m)
     Tz = np.array(P.table, dtype=np.int64)[z.astype(np.int64)].astype(F32)
     sg = np.repeat(step_g, P.block)
-    M = np.repeat(range_M.astype(F32), P.block)
-    return ((Tz * sg).astype(F32) + (-M)).astype(F32)
+    m = np.repeat(_lower(range_M, range_m), P.block)
+    return ((Tz * sg).astype(F32) + m).astype(F32)
 
 
 def compress(P: Params, worker: int, rnd: int, grad: np.ndarray, ef: Optional[np.ndarray],
@@ -391,13 +401,64 @@ def aggregate_stream(P: Params, Y: np.ndarray) -> np.ndarray:
 
 def decompress(P: Params, rnd: int, Y: np.ndarray, range_M: np.ndarray, j0: int = 0) -> np.ndarray:
     """Estimate of the average gradient: m + (Y/n)(M-m)/g, then RHT^-1 (Alg. 2 / Alg. 3).
-    binary32: v = float(Y) * step_n + (-M) with step_n = 2M/(g n); out = (H v) * c * sign."""
+    binary32: v = float(Y) * step_n + m with step_n = (M-m)/(g n), m = -M; out = (H v) * c * sign."""
     _, _, step_n = block_scalars(P, range_M)
     sn = np.repeat(step_n, P.block)
     M = np.repeat(range_M.astype(F32), P.block)
     v = ((Y.astype(F32) * sn).astype(F32) + (-M)).astype(F32)
     signs = rademacher_signs(P.seed, rnd, j0, P.d)
     return irht_blocks(v, signs, P.block)
+
+
+# --------------------------------------------------------------------------- #
+# Uniform THC (Alg. 1): identity table with g = 2^b - 1, range = global minimum and maximum of what is
+# quantized (the gradients themselves, or their RHT when rotation is switched on -- the ablation of App. C).
+# --------------------------------------------------------------------------- #
+def uniform_values(P: Params, rnd: int, grad: np.ndarray, ef: Optional[np.ndarray], rotate: bool) -> np.ndarray:
+    """What a worker quantizes: x = grad + e, rotated block-wise when `rotate`."""
+    x = ef_input(grad, ef)
+    if rotate:
+        x = rht_blocks(x, rademacher_signs(P.seed, rnd, 0, P.d), P.block)
+    return x
+
+
+def uniform_range(P: Params, rnd: int, grads: Sequence[np.ndarray], efs: Optional[Sequence[np.ndarray]],
+                  rotate: bool) -> Tuple[np.ndarray, np.ndarray]:
+    """Preliminary stage of Alg. 1: (m_k, M_k) = (min, max) over all workers of block k."""
+    lo = np.full(P.K, np.inf, dtype=F32)
+    hi = np.full(P.K, -np.inf, dtype=F32)
+    for i in range(P.n):
+        v = uniform_values(P, rnd, grads[i], None if efs is None else efs[i], rotate).reshape(P.K, P.block)
+        lo = np.minimum(lo, v.min(axis=1))
+        hi = np.maximum(hi, v.max(axis=1))
+    return lo, hi
+
+
+def uniform_compress(P: Params, worker: int, rnd: int, grad: np.ndarray, ef: Optional[np.ndarray],
+                     range_m: np.ndarray, range_M: np.ndarray, rotate: bool):
+    """Main stage of Alg. 1, worker side: X_i = USQ(x_i, m, M, b), packed; with error feedback
+    e' = x - D(X_i) (through RHT^-1 when rotated).  P must carry the identity table (g = 2^b - 1)."""
+    assert list(P.table) == list(range(2 ** P.b)) and P.g == 2 ** P.b - 1
+    x = ef_input(grad, ef)
+    v = uniform_values(P, rnd, grad, ef, rotate)
+    z = quantize_rotated(P, v, range_M, sq_halfwords(P.seed, rnd, worker, 0, P.d), range_m)
+    new_ef = None
+    if ef is not None:
+        X = dequantize_indices(P, z, range_M, range_m)
+        if rotate:
+            X = irht_blocks(X, rademacher_signs(P.seed, rnd, 0, P.d), P.block)
+        new_ef = (x - X).astype(F32)
+    return pack_indices(z, P.b), new_ef
+
+
+def uniform_decompress(P: Params, rnd: int, Y: np.ndarray, range_m: np.ndarray, range_M: np.ndarray,
+                       rotate: bool) -> np.ndarray:
+    """Alg. 1's estimate m + (1/n) X (M-m)/(2^b-1) (then RHT^-1 when rotated); X is the integer sum."""
+    _, _, step_n = block_scalars(P, range_M, range_m)
+    v = ((Y.astype(F32) * np.repeat(step_n, P.block)).astype(F32) + np.repeat(range_m.astype(F32), P.block)).astype(F32)
+    if rotate:
+        v = irht_blocks(v, rademacher_signs(P.seed, rnd, 0, P.d), P.block)
+    return v
 
 
 def thc_round(P: Params, rnd: int, grads: Sequence[np.ndarray],
