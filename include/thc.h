@@ -117,6 +117,31 @@ int thc_aggregate(const thc_params* p, const uint8_t* const* packed /* host */, 
 int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const float* range_M,
                    float* out, void* ws, void* stream);
 
+/* ---- Uniform THC (Alg. 1; Sec. 4.2 "Homomorphic USQ") -----------------------------------------------
+ * The simplified variant the paper generalises: 2^b uniformly spaced quantization values on the GLOBAL
+ * range [m, M] = [min_i min(x_i), max_i max(x_i)] (per block), no lookup table.  `p` must carry the identity
+ * table with g = 2^b - 1 (else THC_ETABLE); p->t_p is ignored.  `rotate` != 0 applies the RHT first (the
+ * "with rotation" arm of the ablation in App. C): the range is then taken over the rotated vectors.
+ * thc_aggregate serves unchanged (with the identity table it sums the indices).  Same pointer, stream,
+ * workspace and error conventions as above. */
+
+/* Preliminary stage of Alg. 1: every worker's min / max, then the global ones.
+ *   range_m, range_M   device, d/block floats each, written.
+ * With rotate != 0 the fully rotated vectors of all workers are left in `ws` for thc_uniform_compress. */
+int thc_uniform_prepare_range(const thc_params* p, uint64_t round, const void* const* grads /* host */,
+                              const float* const* ef /* host or NULL */, int rotate, float* range_m,
+                              float* range_M, void* ws, void* stream);
+
+/* Main stage of Alg. 1, worker side: X_i = USQ(x_i, m, M, b), packed.  With ef_inout:
+ * e <- (grad + e) - D(X_i), through RHT^-1 when rotate != 0.  `ws` may be NULL when rotate == 0. */
+int thc_uniform_compress(const thc_params* p, uint32_t worker_id, uint64_t round, const void* grad,
+                         float* ef_inout, int rotate, const float* range_m, const float* range_M,
+                         uint8_t* packed_out, void* ws, void* stream);
+
+/* Alg. 1's estimate m + (1/n) X (M - m)/(2^b - 1) from the aggregated sums X (then RHT^-1 when rotate != 0). */
+int thc_uniform_decompress(const thc_params* p, uint64_t round, const void* agg, int rotate,
+                           const float* range_m, const float* range_M, float* out, void* ws, void* stream);
+
 /* ---- host-side helpers (no GPU work) ------------------------------------------------------------- */
 
 /* t_p = Phi^-1(1 - p/2) (Sec. 5.1), 0 < p < 1. */

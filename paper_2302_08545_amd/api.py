@@ -13,7 +13,8 @@ THC_MAX_WORKERS = 64
 THC_DTYPE_F32, THC_DTYPE_BF16 = 0, 1
 
 EXPORTS = ("thc_version", "thc_strerror", "thc_workspace_bytes", "thc_prepare_range", "thc_compress",
-           "thc_aggregate", "thc_decompress", "thc_threshold", "thc_solve_table")
+           "thc_aggregate", "thc_decompress", "thc_uniform_prepare_range", "thc_uniform_compress",
+           "thc_uniform_decompress", "thc_threshold", "thc_solve_table")
 
 
 class thc_params(C.Structure):
@@ -46,6 +47,9 @@ def lib():
         L.thc_compress.argtypes = [pp, u32, u64, vp, vp, vp, vp, vp, vp]
         L.thc_aggregate.argtypes = [pp, C.POINTER(vp), vp, vp]
         L.thc_decompress.argtypes = [pp, u64, vp, vp, vp, vp, vp]
+        L.thc_uniform_prepare_range.argtypes = [pp, u64, C.POINTER(vp), C.POINTER(vp), C.c_int, vp, vp, vp, vp]
+        L.thc_uniform_compress.argtypes = [pp, u32, u64, vp, vp, C.c_int, vp, vp, vp, vp, vp]
+        L.thc_uniform_decompress.argtypes = [pp, u64, vp, C.c_int, vp, vp, vp, vp, vp]
         L.thc_threshold.restype = C.c_double
         L.thc_threshold.argtypes = [C.c_double]
         L.thc_solve_table.argtypes = [u32, u32, C.c_double, C.POINTER(C.c_uint8), C.POINTER(C.c_double)]
@@ -120,6 +124,26 @@ def thc_aggregate(p: thc_params, packed, agg_out, stream=None) -> None:
 def thc_decompress(p: thc_params, rnd: int, agg, range_M, out, ws, stream=None) -> None:
     _check(lib().thc_decompress(C.byref(p), rnd, _ptr(agg), _ptr(range_M), _ptr(out), _ptr(ws), _stream(stream)),
            "thc_decompress")
+
+
+def thc_uniform_prepare_range(p: thc_params, rnd: int, grads, ef, rotate: bool, range_m, range_M, ws,
+                              stream=None) -> None:
+    _check(lib().thc_uniform_prepare_range(C.byref(p), rnd, _ptr_array(grads), _ptr_array(ef), int(rotate),
+                                           _ptr(range_m), _ptr(range_M), _ptr(ws), _stream(stream)),
+           "thc_uniform_prepare_range")
+
+
+def thc_uniform_compress(p: thc_params, worker_id: int, rnd: int, grad, ef_inout, rotate: bool, range_m, range_M,
+                         packed_out, ws, stream=None) -> None:
+    _check(lib().thc_uniform_compress(C.byref(p), worker_id, rnd, _ptr(grad), _ptr(ef_inout), int(rotate),
+                                      _ptr(range_m), _ptr(range_M), _ptr(packed_out), _ptr(ws), _stream(stream)),
+           "thc_uniform_compress")
+
+
+def thc_uniform_decompress(p: thc_params, rnd: int, agg, rotate: bool, range_m, range_M, out, ws,
+                           stream=None) -> None:
+    _check(lib().thc_uniform_decompress(C.byref(p), rnd, _ptr(agg), int(rotate), _ptr(range_m), _ptr(range_M),
+                                        _ptr(out), _ptr(ws), _stream(stream)), "thc_uniform_decompress")
 
 
 def thc_threshold(p: float) -> float:

@@ -72,6 +72,18 @@ size_t ws_x_bytes(const thc_params* p) { return (size_t)p->n * (size_t)p->d * si
 
 uint64_t tiles_of(uint64_t d) { return (d + TILE - 1) / TILE; }
 
+void fill_lut(const thc_params* p, uint32_t (&lut)[256]) {
+  const uint32_t top = (1u << p->b) - 1;
+  for (uint32_t k = 0; k < 256; ++k) {
+    const uint32_t kk = k < p->g ? k : p->g;
+    uint32_t z0 = 0;
+    while (z0 < top && p->table[z0 + 1] <= kk) ++z0;
+    const uint32_t lo = p->table[z0];
+    const uint32_t wd = z0 < top ? (uint32_t)(p->table[z0 + 1] - lo) : 255u;   // 255: the top value never rounds up
+    lut[k] = lo | wd << 8 | z0 << 16;
+  }
+}
+
 int check_launch() {
   const hipError_t e = hipGetLastError();
   if (e == hipSuccess) return THC_OK;
@@ -101,6 +113,9 @@ template <int R> struct LaunchQuant {
     if (cfold && R >= 2) k_fwd_hi_quant<R, true><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a);
     else k_fwd_hi_quant<R, false><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a);
   }
+};
+template <int R> struct LaunchHiStore {
+  static void run(const HiStoreArgs& a, uint64_t tiles, hipStream_t s) { k_fwd_hi_store<R><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a); }
 };
 template <int R> struct LaunchInvHi {
   static void run(const InvHiArgs& a, uint64_t tiles, hipStream_t s) { k_inv_hi<R><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a); }
@@ -186,7 +201,7 @@ int thc_workspace_bytes(const thc_params* p, size_t* bytes_out) {
   if (rc) return rc;
   if (!bytes_out) return THC_EINVAL;
   const Plan pl = make_plan(p->block);
-  *bytes_out = ws_x_bytes(p) + partial_count(p, pl) * sizeof(double) + 256;
+  *bytes_out = ws_x_bytes(p) + partial_count(p, pl) * (sizeof(double) + 2 * sizeof(float)) + 256;
   return THC_OK;
 }
 
@@ -248,16 +263,7 @@ int thc_compress(const thc_params* p, uint32_t worker_id, uint64_t round, const 
   q.k0 = (uint32_t)p->seed;
   q.k1 = (uint32_t)(p->seed >> 32);
   q.c = (float)(1.0 / std::sqrt((double)p->block));
-  // per grid cell k: the largest index z0 with T[z0] <= k, its value lo and the gap wd to the next value
-  const uint32_t top = (1u << p->b) - 1;
-  for (uint32_t k = 0; k < 256; ++k) {
-    const uint32_t kk = k < p->g ? k : p->g;
-    uint32_t z0 = 0;
-    while (z0 < top && p->table[z0 + 1] <= kk) ++z0;
-    const uint32_t lo = p->table[z0];
-    const uint32_t wd = z0 < top ? (uint32_t)(p->table[z0 + 1] - lo) : 255u;   // 255: the top value never rounds up
-    q.lut[k] = lo | wd << 8 | z0 << 16;
-  }
+  fill_lut(p, q.lut);   // per grid cell k: the largest index z0 with T[z0] <= k, its value and the gap to the next
   dispatch_0_7<LaunchQuant>(pl.R, q, (pl.L & 1) == 0, tiles_of(p->d), s);
 
   if (ef_inout) {
@@ -326,6 +332,160 @@ int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const f
   InvLoArgs lo{};
   lo.src = agg;
   lo.range_M = range_M;
+  lo.ws_x = wsx;
+  lo.d = p->d;
+  lo.L = (uint32_t)pl.L;
+  lo.src_bits = p->agg_bits;
+  lo.use_table = 0;
+  lo.divisor = p->g * p->n;
+  InvHiArgs hi{};
+  hi.out = out;
+  hi.round = (uint32_t)round;
+  hi.k0 = (uint32_t)p->seed;
+  hi.k1 = (uint32_t)(p->seed >> 32);
+  hi.mode = 0;
+  return run_inverse(p, pl, lo, wsx, hi, s);
+}
+
+// ---- uniform THC (Alg. 1) -----------------------------------------------------------------------
+
+namespace {
+
+int validate_uniform(const thc_params* p) {
+  const int rc = validate(p);
+  if (rc) return rc;
+  if (p->g != (1u << p->b) - 1) return THC_ETABLE;     // identity table: T[z] = z (checked by validate: strictly increasing 0..g)
+  return THC_OK;
+}
+
+float* pmin_of(const thc_params* p, const Plan& pl, void* ws) {
+  return reinterpret_cast<float*>(static_cast<char*>(ws) + ws_x_bytes(p) + partial_count(p, pl) * sizeof(double));
+}
+
+}  // namespace
+
+int thc_uniform_prepare_range(const thc_params* p, uint64_t round, const void* const* grads, const float* const* ef,
+                              int rotate, float* range_m, float* range_M, void* ws, void* stream) {
+  const int rc = validate_uniform(p);
+  if (rc) return rc;
+  if (!grads || !ws || !aligned16(ws) || round >> 32 || !range_m || !range_M) return THC_EINVAL;
+  for (uint32_t i = 0; i < p->n; ++i) {
+    if (!grads[i] || !aligned16(grads[i])) return THC_EINVAL;
+    if (ef && (!ef[i] || !aligned16(ef[i]))) return THC_EINVAL;
+  }
+  const Plan pl = make_plan(p->block);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* pmin = pmin_of(p, pl, ws);
+  float* pmax = pmin + partial_count(p, pl);
+  const size_t per_worker = (size_t)(p->d >> pl.L1);
+  const bool bf16 = p->in_dtype == THC_DTYPE_BF16;
+  if (rotate) {
+    // full forward RHT of every worker, kept in the workspace
+    const int r0 = thc_prepare_range(p, round, grads, ef, nullptr, ws, stream);
+    if (r0) return r0;
+    for (uint32_t i = 0; i < p->n; ++i) {
+      float* wsx = static_cast<float*>(ws) + (size_t)i * p->d;
+      run_mids(pl, wsx, p->d, s);
+      HiStoreArgs h{wsx, pmin + i * per_worker, pmax + i * per_worker, p->d, pl.s0_hi, (uint32_t)pl.L,
+                    (float)(1.0 / std::sqrt((double)p->block))};
+      dispatch_0_7<LaunchHiStore>(pl.R, h, tiles_of(p->d), s);
+    }
+  } else {
+    MinMaxArgs a{};
+    for (uint32_t i = 0; i < p->n; ++i) {
+      a.grads.p[i] = grads[i];
+      if (ef) a.efs.p[i] = ef[i];
+    }
+    a.pmin = pmin;
+    a.pmax = pmax;
+    a.d = p->d;
+    a.L1 = (uint32_t)pl.L1;
+    const dim3 grid((unsigned)tiles_of(p->d), p->n), blk(NT);
+    if (bf16) { if (ef) k_minmax<true, true><<<grid, blk, 0, s>>>(a); else k_minmax<true, false><<<grid, blk, 0, s>>>(a); }
+    else { if (ef) k_minmax<false, true><<<grid, blk, 0, s>>>(a); else k_minmax<false, false><<<grid, blk, 0, s>>>(a); }
+  }
+  MinMaxFinalArgs f{pmin, pmax, range_m, range_M, p->d, p->n, (uint32_t)pl.L, (uint32_t)pl.L1};
+  k_minmax_final<<<dim3((unsigned)(p->d / p->block)), dim3(64), 0, s>>>(f);
+  return check_launch();
+}
+
+int thc_uniform_compress(const thc_params* p, uint32_t worker_id, uint64_t round, const void* grad, float* ef_inout,
+                         int rotate, const float* range_m, const float* range_M, uint8_t* packed_out, void* ws,
+                         void* stream) {
+  const int rc = validate_uniform(p);
+  if (rc) return rc;
+  if (worker_id >= p->n || round >> 32 || !range_m || !range_M || !packed_out || !aligned16(packed_out)) return THC_EINVAL;
+  if (rotate && (!ws || !aligned16(ws))) return THC_EINVAL;
+  if (!rotate && (!grad || !aligned16(grad))) return THC_EINVAL;
+  if (ef_inout && (!grad || !aligned16(grad) || !aligned16(ef_inout))) return THC_EINVAL;
+  const Plan pl = make_plan(p->block);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* wsx = rotate ? static_cast<float*>(ws) + (size_t)worker_id * p->d : nullptr;
+  UQuantArgs q{};
+  q.x = wsx;
+  q.grad = grad;
+  q.ef = rotate ? nullptr : ef_inout;
+  q.range_M = range_M;
+  q.range_m = range_m;
+  q.packed = packed_out;
+  q.d = p->d;
+  q.L = (uint32_t)pl.L;
+  q.b = p->b;
+  q.g = p->g;
+  q.round = (uint32_t)round;
+  q.worker = worker_id;
+  q.k0 = (uint32_t)p->seed;
+  q.k1 = (uint32_t)(p->seed >> 32);
+  q.ef_update = (!rotate && ef_inout) ? 1u : 0u;
+  fill_lut(p, q.lut);
+  const dim3 grid((unsigned)tiles_of(p->d)), blk(NT);
+  if (p->in_dtype == THC_DTYPE_BF16) k_uniform_quant<true><<<grid, blk, 0, s>>>(q);
+  else k_uniform_quant<false><<<grid, blk, 0, s>>>(q);
+  if (rotate && ef_inout) {
+    // e <- (grad + e) - RHT^-1(X_i): rebuild X_i from the indices, inverse transform, subtract
+    InvLoArgs lo{};
+    lo.src = packed_out;
+    lo.range_M = range_M;
+    lo.range_m = range_m;
+    lo.ws_x = wsx;
+    lo.d = p->d;
+    lo.L = (uint32_t)pl.L;
+    lo.src_bits = p->b;
+    lo.use_table = 1;
+    lo.divisor = p->g;
+    std::memcpy(lo.table, p->table, 256);
+    InvHiArgs hi{};
+    hi.out = ef_inout;
+    hi.grad = grad;
+    hi.round = (uint32_t)round;
+    hi.k0 = q.k0;
+    hi.k1 = q.k1;
+    hi.mode = 1;
+    hi.bf16 = p->in_dtype == THC_DTYPE_BF16;
+    return run_inverse(p, pl, lo, wsx, hi, s);
+  }
+  return check_launch();
+}
+
+int thc_uniform_decompress(const thc_params* p, uint64_t round, const void* agg, int rotate, const float* range_m,
+                           const float* range_M, float* out, void* ws, void* stream) {
+  const int rc = validate_uniform(p);
+  if (rc) return rc;
+  if (round >> 32 || !agg || !range_m || !range_M || !out || !aligned16(agg) || !aligned16(out)) return THC_EINVAL;
+  if (rotate && (!ws || !aligned16(ws))) return THC_EINVAL;
+  const Plan pl = make_plan(p->block);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!rotate) {
+    UDequantArgs a{agg, range_M, range_m, out, p->d, (uint32_t)pl.L, p->agg_bits, p->g * p->n};
+    const uint64_t threads = p->d / 16;
+    k_uniform_dequant<<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s>>>(a);
+    return check_launch();
+  }
+  float* wsx = static_cast<float*>(ws);
+  InvLoArgs lo{};
+  lo.src = agg;
+  lo.range_M = range_M;
+  lo.range_m = range_m;
   lo.ws_x = wsx;
   lo.d = p->d;
   lo.L = (uint32_t)pl.L;

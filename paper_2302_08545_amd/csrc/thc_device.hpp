@@ -107,7 +107,7 @@ __device__ __forceinline__ void lds_round(const float* lds, int t, Sink&& sink) 
   constexpr int E = 1 << NB;
   constexpr int G = 16 >> NB;
   // physical distance between consecutive gathered values (PLAIN / PAD only)
-  constexpr int ESTR = (LY == PAD && P >= 6) ? (1 << P) + 4 * (1 << (P - 6)) : (1 << P);
+  constexpr int ESTR = (LY == PAD && P >= 6) ? (1 << P) + 4 * ((1 << P) >> 6) : (1 << P);
   static_assert(LY != PAD || P >= 6 || P + NB <= 6, "a padded gather must not straddle a 64-value group");
 #pragma unroll
   for (int gi = 0; gi < G; ++gi) {

@@ -348,6 +348,7 @@ __global__ __launch_bounds__(NT) void k_mid(const MidArgs a) {
 struct QuantArgs {
   const float* x;          // one worker's half-rotated vector, d floats
   const float* range_M;    // K floats
+  const float* range_m;    // K floats, or null: m = -M
   uint8_t* packed;         // d*b/8 bytes
   uint64_t d;
   int s0;                  // log2 of the row pitch
@@ -359,7 +360,7 @@ struct QuantArgs {
 };
 
 struct QuantScalars {
-  float M, negM, sc16, c;  // for even log2 B: M and sc16 are pre-divided / pre-multiplied by c, and c is unused
+  float M, lo, sc16, c;  // range [lo, M]; for even log2 B they and sc16 are pre-scaled by c, and c is unused
 };
 
 template <bool CFOLD>
@@ -369,8 +370,8 @@ __device__ __forceinline__ void quantize8(const float (&hv)[8], const uint4 rnd,
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const float v = CFOLD ? hv[e] : hv[e] * s.c;
-    const float xc = __builtin_amdgcn_fmed3f(v, s.negM, s.M);
-    const float y16 = (xc + s.M) * s.sc16;
+    const float xc = __builtin_amdgcn_fmed3f(v, s.lo, s.M);
+    const float y16 = (xc - s.lo) * s.sc16;
     const uint32_t ki = (uint32_t)y16;
     const uint2 ent = lut[(ki >> 16) & 255u];
     const float t16 = y16 - __uint_as_float(ent.x);
@@ -413,15 +414,21 @@ __device__ __forceinline__ void build_quant_lut(const QuantArgs& a, uint2* lut, 
   }
 }
 
-__device__ __forceinline__ float scale16_of(float M, uint32_t g) {
-  return M > 0.f ? (float)((double)g / (2.0 * (double)M)) * 65536.0f : 0.f;
+// g / (M - m) * 2^16: the width in binary64, the quotient rounded once to binary32 (0 for an empty range)
+__device__ __forceinline__ float scale16_of(float M, float m, uint32_t g) {
+  const double W = (double)M - (double)m;
+  return W > 0.0 ? (float)((double)g / W) * 65536.0f : 0.f;
+}
+
+__device__ __forceinline__ float lower_of(const float* range_m, uint64_t blk, float M) {
+  return range_m ? range_m[blk] : -M;
 }
 
 template <int R, bool CFOLD>
 __global__ __launch_bounds__(NT) void k_fwd_hi_quant(const QuantArgs a) {
   __shared__ __align__(16) float lds[TILE];
   __shared__ uint2 lut[256];
-  __shared__ float sM[8], sScale[8];
+  __shared__ float sM[8], sLo[8], sScale[8];
 
   const int t = threadIdx.x;
 
@@ -431,9 +438,11 @@ __global__ __launch_bounds__(NT) void k_fwd_hi_quant(const QuantArgs a) {
     hi_issue_loads<R>(a.x, g, t, x);            // tile loads first: everything below overlaps their latency
     build_quant_lut(a, lut, t);
     if (t == 0) {                               // the whole tile lies in one block
-      const float M = a.range_M[g.base >> a.L];
-      const float sc = scale16_of(M, a.g);
+      const uint64_t blk = g.base >> a.L;
+      const float M = a.range_M[blk], m = lower_of(a.range_m, blk, M);
+      const float sc = scale16_of(M, m, a.g);
       sM[0] = CFOLD ? M * (1.0f / a.c) : M;
+      sLo[0] = CFOLD ? m * (1.0f / a.c) : m;
       sScale[0] = CFOLD ? sc * a.c : sc;
     }
     hi_r0_to_lds<R>(x, lds, t);
@@ -441,7 +450,7 @@ __global__ __launch_bounds__(NT) void k_fwd_hi_quant(const QuantArgs a) {
     int idx[2];
     float v[2][8];
     hi_back<R>(lds, t, idx, v);
-    const QuantScalars s{sM[0], -sM[0], sScale[0], a.c};
+    const QuantScalars s{sM[0], sLo[0], sScale[0], a.c};
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const uint64_t j = g.coord(idx[h]);
@@ -458,10 +467,11 @@ __global__ __launch_bounds__(NT) void k_fwd_hi_quant(const QuantArgs a) {
     const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
     if (t < nblk) {
       const uint64_t blk = (g.base >> a.L) + t;
-      float M = 0.f;
-      if (blk < (a.d >> a.L)) M = a.range_M[blk];
+      float M = 0.f, m = 0.f;
+      if (blk < (a.d >> a.L)) { M = a.range_M[blk]; m = lower_of(a.range_m, blk, M); }
       sM[t] = M;
-      sScale[t] = scale16_of(M, a.g);
+      sLo[t] = m;
+      sScale[t] = scale16_of(M, m, a.g);
     }
     hi_load_to_lds<R>(a.x, g, a.d, lds, t);
     lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, float) {});
@@ -472,7 +482,7 @@ __global__ __launch_bounds__(NT) void k_fwd_hi_quant(const QuantArgs a) {
       const uint64_t j = g.coord(idx);
       if (j >= a.d) continue;
       const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
-      const QuantScalars s{sM[bt], -sM[bt], sScale[bt], a.c};
+      const QuantScalars s{sM[bt], sLo[bt], sScale[bt], a.c};
       const float4 p0 = *reinterpret_cast<const float4*>(&lds[idx]);
       const float4 p1 = *reinterpret_cast<const float4*>(&lds[idx + 4]);
       const float hv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
@@ -486,6 +496,58 @@ __global__ __launch_bounds__(NT) void k_fwd_hi_quant(const QuantArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Sixteen consecutive codes (table indices or aggregated sums) of `bits` bits each, starting at
+// coordinate j (a multiple of 16): codes_load fetches the raw words (for the widths with a fast path)
+// or the decoded fields (any other width); codes_decode finishes the fast paths.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void codes_load(const uint8_t* s8, uint32_t bits, uint64_t j, uint32_t (&w)[8],
+                                           uint32_t (&y)[16]) {
+  if (bits == 8) {
+    const uint4 r = *reinterpret_cast<const uint4*>(s8 + j);
+    w[0] = r.x; w[1] = r.y; w[2] = r.z; w[3] = r.w;
+  } else if (bits == 16) {
+    const uint4 r0 = *reinterpret_cast<const uint4*>(s8 + 2 * j);
+    const uint4 r1 = *reinterpret_cast<const uint4*>(s8 + 2 * j + 16);
+    w[0] = r0.x; w[1] = r0.y; w[2] = r0.z; w[3] = r0.w; w[4] = r1.x; w[5] = r1.y; w[6] = r1.z; w[7] = r1.w;
+  } else if (bits == 4) {
+    const uint2 r = *reinterpret_cast<const uint2*>(s8 + (j >> 1));
+    w[0] = r.x; w[1] = r.y;
+  } else if (bits == 2) {
+    w[0] = *reinterpret_cast<const uint32_t*>(s8 + (j >> 2));
+  } else if (bits == 1) {
+    w[0] = *reinterpret_cast<const uint16_t*>(s8 + (j >> 3));
+  } else {   // any other width: eight fields take `bits` bytes
+    uint32_t z0[8], z1[8];
+    load_fields8(s8 + (j >> 3) * bits, bits, z0);
+    load_fields8(s8 + ((j >> 3) + 1) * bits, bits, z1);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { y[e] = z0[e]; y[8 + e] = z1[e]; }
+  }
+}
+
+__device__ __forceinline__ void codes_decode(uint32_t bits, bool ok, const uint32_t (&w)[8], uint32_t (&y)[16]) {
+  if (bits == 8) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 2] >> (8 * (e & 3))) & 255u;
+  } else if (bits == 16) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+  } else if (bits == 4) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 3] >> (4 * (e & 7))) & 15u;
+  } else if (bits == 2) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[0] >> (2 * e)) & 3u;
+  } else if (bits == 1) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[0] >> e) & 1u;
+  } else if (!ok) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = 0;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Inverse "lo" pass.  Source is either the aggregated stream (decompression, Alg. 2:
 // m + (Y/n)(M-m)/g = Y * step_n - M) or one worker's packed indices (error feedback, Alg. 3:
 // X_i = m + T[z](M-m)/g = T[z] * step_g - M).  One thread loads 16 consecutive coordinates.
@@ -493,6 +555,7 @@ __global__ __launch_bounds__(NT) void k_fwd_hi_quant(const QuantArgs a) {
 struct InvLoArgs {
   const void* src;         // aggregated stream or packed indices
   const float* range_M;
+  const float* range_m;    // or null: m = -M
   float* ws_x;             // d floats, written
   uint64_t d;
   uint32_t L;
@@ -518,70 +581,27 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
   // raw bits first, so the load is in flight while the block constants are prepared
   uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   uint32_t y[16];
-  const uint8_t* s8 = static_cast<const uint8_t*>(a.src);
-  const bool fast = a.src_bits == 8 || a.src_bits == 16 || a.src_bits == 4 || a.src_bits == 2 || a.src_bits == 1;
-  if (ok) {
-    if (a.src_bits == 8) {
-      const uint4 r = *reinterpret_cast<const uint4*>(s8 + j);
-      w[0] = r.x; w[1] = r.y; w[2] = r.z; w[3] = r.w;
-    } else if (a.src_bits == 16) {
-      const uint4 r0 = *reinterpret_cast<const uint4*>(s8 + 2 * j);
-      const uint4 r1 = *reinterpret_cast<const uint4*>(s8 + 2 * j + 16);
-      w[0] = r0.x; w[1] = r0.y; w[2] = r0.z; w[3] = r0.w; w[4] = r1.x; w[5] = r1.y; w[6] = r1.z; w[7] = r1.w;
-    } else if (a.src_bits == 4) {
-      const uint2 r = *reinterpret_cast<const uint2*>(s8 + (j >> 1));
-      w[0] = r.x; w[1] = r.y;
-    } else if (a.src_bits == 2) {
-      w[0] = *reinterpret_cast<const uint32_t*>(s8 + (j >> 2));
-    } else if (a.src_bits == 1) {
-      w[0] = *reinterpret_cast<const uint16_t*>(s8 + (j >> 3));
-    } else {   // any other width: eight fields take src_bits bytes
-      uint32_t z0[8], z1[8];
-      load_fields8(s8 + (j >> 3) * a.src_bits, a.src_bits, z0);
-      load_fields8(s8 + ((j >> 3) + 1) * a.src_bits, a.src_bits, z1);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { y[e] = z0[e]; y[8 + e] = z1[e]; }
-    }
-  }
+  if (ok) codes_load(static_cast<const uint8_t*>(a.src), a.src_bits, j, w, y);
 
   const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
   if (t < nblk) {
     const uint64_t blk = (off >> a.L) + t;
-    float M = 0.f;
-    if (blk < (a.d >> a.L)) M = a.range_M[blk];
-    sM[t] = M;
-    sStep[t] = (float)((2.0 * (double)M) / (double)a.divisor);
+    float M = 0.f, m = 0.f;
+    if (blk < (a.d >> a.L)) { M = a.range_M[blk]; m = lower_of(a.range_m, blk, M); }
+    sM[t] = m;                                                   // the affine map only needs the lower end
+    sStep[t] = (float)(((double)M - (double)m) / (double)a.divisor);
   }
   if (a.use_table && t < 256) tabf[t] = (float)a.table[t];
   __syncthreads();
 
-  if (a.src_bits == 8) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 2] >> (8 * (e & 3))) & 255u;
-  } else if (a.src_bits == 16) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-  } else if (a.src_bits == 4) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 3] >> (4 * (e & 7))) & 15u;
-  } else if (a.src_bits == 2) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = (w[0] >> (2 * e)) & 3u;
-  } else if (a.src_bits == 1) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = (w[0] >> e) & 1u;
-  } else if (!ok) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = 0;
-  }
-  (void)fast;
+  codes_decode(a.src_bits, ok, w, y);
   const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
-  const float negM = -sM[bt], step = sStep[bt];
+  const float lo = sM[bt], step = sStep[bt];
   float v[16];
 #pragma unroll
   for (int e = 0; e < 16; ++e) {
     const float f = a.use_table ? tabf[y[e]] : (float)y[e];
-    v[e] = ok ? f * step + negM : 0.f;
+    v[e] = ok ? f * step + lo : 0.f;
   }
   bfly<4>(v);
 #pragma unroll
@@ -665,6 +685,289 @@ __global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
       *reinterpret_cast<float4*>(a.out + j) = inv_finish4(v, bits, a, j);
     }
   }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Uniform THC (Alg. 1).  Preliminary stage: every worker's minimum and maximum per block, then the
+// global ones.  Main stage: uniform stochastic quantization = the same quantizer with the identity
+// table, on the gradients themselves or (ablation of App. C) on their RHT.
+// Partial minima / maxima: one per min(B, 8192) coordinates per worker, like the partial sums of squares.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) v = __builtin_fminf(v, __shfl_xor(v, m, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) v = __builtin_fmaxf(v, __shfl_xor(v, m, 64));
+  return v;
+}
+
+struct MinMaxArgs {
+  PtrArr grads;
+  PtrArr efs;
+  float* pmin;       // n * (d >> L1)
+  float* pmax;
+  uint64_t d;
+  uint32_t L1;       // log2 of min(B, 8192)
+};
+
+template <bool BF16, bool EF>
+__global__ __launch_bounds__(NT) void k_minmax(const MinMaxArgs a) {
+  __shared__ float smin[32], smax[32];   // one per 256 consecutive coordinates of the tile
+  const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
+  const uint32_t worker = blockIdx.y;
+  const uint64_t off = (uint64_t)blockIdx.x << LOG_TILE;
+  const float* ef = EF ? static_cast<const float*>(a.efs.p[worker]) : nullptr;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint64_t j = off + 4u * (uint32_t)(i * NT + t);
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+    if (j < a.d) {
+      float4 x = load_grad4<BF16>(a.grads.p[worker], j);
+      if constexpr (EF) {
+        const float4 e = *reinterpret_cast<const float4*>(ef + j);
+        x.x += e.x; x.y += e.y; x.z += e.z; x.w += e.w;
+      }
+      mn = __builtin_fminf(__builtin_fminf(x.x, x.y), __builtin_fminf(x.z, x.w));
+      mx = __builtin_fmaxf(__builtin_fmaxf(x.x, x.y), __builtin_fmaxf(x.z, x.w));
+    }
+    mn = wave_min(mn);
+    mx = wave_max(mx);
+    if (lane == 0) { smin[i * 8 + wave] = mn; smax[i * 8 + wave] = mx; }
+  }
+  __syncthreads();
+  const int nblk = TILE >> a.L1, cpb = 32 / nblk;   // chunks of 256 per block inside the tile
+  if (t < nblk) {
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+    for (int c = 0; c < cpb; ++c) {
+      mn = __builtin_fminf(mn, smin[t * cpb + c]);
+      mx = __builtin_fmaxf(mx, smax[t * cpb + c]);
+    }
+    const uint64_t pidx = (off >> a.L1) + t;
+    if (pidx < (a.d >> a.L1)) {
+      a.pmin[(uint64_t)worker * (a.d >> a.L1) + pidx] = mn;
+      a.pmax[(uint64_t)worker * (a.d >> a.L1) + pidx] = mx;
+    }
+  }
+}
+
+struct MinMaxFinalArgs {
+  const float* pmin;
+  const float* pmax;
+  float* range_m;
+  float* range_M;
+  uint64_t d;
+  uint32_t n, L, L1;
+};
+
+__global__ __launch_bounds__(64) void k_minmax_final(const MinMaxFinalArgs a) {
+  const uint64_t k = blockIdx.x;
+  const int lane = threadIdx.x;
+  const uint32_t ppb = 1u << (a.L - a.L1);
+  const uint64_t per_worker = a.d >> a.L1;
+  float mn = __builtin_inff(), mx = -__builtin_inff();
+  for (uint32_t i = 0; i < a.n; ++i) {
+    const uint64_t base = (uint64_t)i * per_worker + k * ppb;
+    for (uint32_t j = lane; j < ppb; j += 64) {
+      mn = __builtin_fminf(mn, a.pmin[base + j]);
+      mx = __builtin_fmaxf(mx, a.pmax[base + j]);
+    }
+  }
+  mn = wave_min(mn);
+  mx = wave_max(mx);
+  if (lane == 0) { a.range_m[k] = mn; a.range_M[k] = mx; }
+}
+
+// Last strided pass of a forward RHT that keeps the rotated vector: finishes the butterflies, scales by
+// 1/sqrt(B), writes the result back in place and records the tile's minimum and maximum.
+struct HiStoreArgs {
+  float* x;          // one worker's half-rotated vector, d floats, rotated in place
+  float* pmin;       // this worker's partial minima, d >> L1 floats
+  float* pmax;
+  uint64_t d;
+  int s0;
+  uint32_t L;
+  float c;
+};
+
+template <int R>
+__global__ __launch_bounds__(NT) void k_fwd_hi_store(const HiStoreArgs a) {
+  __shared__ __align__(16) float lds[TILE];
+  __shared__ float smin[16], smax[16];
+  const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
+  const HiGeom<R> g(blockIdx.x, a.s0);
+  if constexpr (R >= 2) {
+    hi_front<R>(a.x, g, lds, t);
+    int idx[2];
+    float v[2][8];
+    hi_back<R>(lds, t, idx, v);
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        v[h][e] *= a.c;
+        mn = __builtin_fminf(mn, v[h][e]);
+        mx = __builtin_fmaxf(mx, v[h][e]);
+      }
+      float* o = a.x + g.coord(idx[h]);
+      *reinterpret_cast<float4*>(o) = make_float4(v[h][0], v[h][1], v[h][2], v[h][3]);
+      *reinterpret_cast<float4*>(o + 4) = make_float4(v[h][4], v[h][5], v[h][6], v[h][7]);
+    }
+    mn = wave_min(mn);
+    mx = wave_max(mx);
+    if (lane == 0) { smin[wave] = mn; smax[wave] = mx; }
+    __syncthreads();
+    if (t == 0) {   // the whole tile lies in one block: one partial per tile
+      for (int w = 1; w < 8; ++w) { mn = __builtin_fminf(mn, smin[w]); mx = __builtin_fmaxf(mx, smax[w]); }
+      a.pmin[blockIdx.x] = mn;
+      a.pmax[blockIdx.x] = mx;
+    }
+  } else {
+    hi_load_to_lds<R>(a.x, g, a.d, lds, t);
+    lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, float) {});
+    __syncthreads();
+    // thread owns tile indices [8(t + 512h), +8): a wave covers 512 consecutive values per h
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int idx = 8 * (t + NT * h);
+      const uint64_t j = g.coord(idx);
+      float mn = __builtin_inff(), mx = -__builtin_inff();
+      if (j < a.d) {
+        float4 p0 = *reinterpret_cast<const float4*>(&lds[idx]);
+        float4 p1 = *reinterpret_cast<const float4*>(&lds[idx + 4]);
+        p0.x *= a.c; p0.y *= a.c; p0.z *= a.c; p0.w *= a.c;
+        p1.x *= a.c; p1.y *= a.c; p1.z *= a.c; p1.w *= a.c;
+        *reinterpret_cast<float4*>(a.x + j) = p0;
+        *reinterpret_cast<float4*>(a.x + j + 4) = p1;
+        mn = __builtin_fminf(__builtin_fminf(__builtin_fminf(p0.x, p0.y), __builtin_fminf(p0.z, p0.w)),
+                             __builtin_fminf(__builtin_fminf(p1.x, p1.y), __builtin_fminf(p1.z, p1.w)));
+        mx = __builtin_fmaxf(__builtin_fmaxf(__builtin_fmaxf(p0.x, p0.y), __builtin_fmaxf(p0.z, p0.w)),
+                             __builtin_fmaxf(__builtin_fmaxf(p1.x, p1.y), __builtin_fmaxf(p1.z, p1.w)));
+      }
+      mn = wave_min(mn);
+      mx = wave_max(mx);
+      if (lane == 0) { smin[h * 8 + wave] = mn; smax[h * 8 + wave] = mx; }
+    }
+    __syncthreads();
+    // blocks inside the tile (B < 8192) or the single one (then R rows of one block share the tile)
+    const uint32_t L1 = a.L < LOG_TILE ? a.L : LOG_TILE;
+    const int nblk = TILE >> L1, cpb = 16 / nblk;    // chunks of 512 per block inside the tile
+    if (t < nblk) {
+      float mn = __builtin_inff(), mx = -__builtin_inff();
+      for (int c = 0; c < cpb; ++c) {
+        mn = __builtin_fminf(mn, smin[t * cpb + c]);
+        mx = __builtin_fmaxf(mx, smax[t * cpb + c]);
+      }
+      const uint64_t pidx = ((uint64_t)blockIdx.x << (LOG_TILE - L1)) + t;
+      if (pidx < (a.d >> L1)) { a.pmin[pidx] = mn; a.pmax[pidx] = mx; }
+    }
+  }
+}
+
+// Uniform stochastic quantization of one worker's vector: 8192 consecutive coordinates per workgroup.
+// Source: the rotated vector `x` when given, else grad (+ e).  Without rotation the error-feedback update
+// e <- x - (m + z (M-m)/g) is done here; with rotation it needs an inverse transform (separate passes).
+struct UQuantArgs {
+  const float* x;          // rotated vector or null
+  const void* grad;
+  float* ef;               // error feedback, read (and written when ef_update) or null
+  const float* range_M;
+  const float* range_m;
+  uint8_t* packed;
+  uint64_t d;
+  uint32_t L, b, g;
+  uint32_t round, worker, k0, k1;
+  uint32_t ef_update;
+  uint32_t lut[256];
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(NT) void k_uniform_quant(const UQuantArgs a) {
+  __shared__ uint2 lut[256];
+  __shared__ float sM[8], sLo[8], sScale[8], sStep[8];
+  const int t = threadIdx.x;
+  const uint64_t off = (uint64_t)blockIdx.x << LOG_TILE;
+  if (t < 256) {
+    const uint32_t ent = a.lut[t];
+    lut[t] = make_uint2(__float_as_uint((float)(ent & 255u) * 65536.0f), ent >> 8);
+  }
+  const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
+  if (t < nblk) {
+    const uint64_t blk = (off >> a.L) + t;
+    float M = 0.f, m = 0.f;
+    if (blk < (a.d >> a.L)) { M = a.range_M[blk]; m = lower_of(a.range_m, blk, M); }
+    sM[t] = M;
+    sLo[t] = m;
+    sScale[t] = scale16_of(M, m, a.g);
+    sStep[t] = (float)(((double)M - (double)m) / (double)a.g);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int idx = 8 * (t + NT * h);
+    const uint64_t j = off + idx;
+    if (j >= a.d) continue;
+    float4 p0, p1;
+    if (a.x) {
+      p0 = *reinterpret_cast<const float4*>(a.x + j);
+      p1 = *reinterpret_cast<const float4*>(a.x + j + 4);
+    } else {
+      p0 = load_grad4<BF16>(a.grad, j);
+      p1 = load_grad4<BF16>(a.grad, j + 4);
+      if (a.ef) {
+        const float4 e0 = *reinterpret_cast<const float4*>(a.ef + j);
+        const float4 e1 = *reinterpret_cast<const float4*>(a.ef + j + 4);
+        p0.x += e0.x; p0.y += e0.y; p0.z += e0.z; p0.w += e0.w;
+        p1.x += e1.x; p1.y += e1.y; p1.z += e1.z; p1.w += e1.w;
+      }
+    }
+    const float hv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+    const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
+    const QuantScalars s{sM[bt], sLo[bt], sScale[bt], 1.0f};
+    const uint64_t q = j >> 3;
+    const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, a.worker, a.k0, a.k1);
+    uint32_t z[8];
+    quantize8<true>(hv, rnd, s, lut, z);          // no scaling: the values are final
+    store_packed8(a.packed, j, a.b, z);
+    if (a.ef_update) {
+      const float step = sStep[bt], lo = sLo[bt];
+      float e[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) e[k] = hv[k] - ((float)z[k] * step + lo);   // identity table: T[z] = z
+      *reinterpret_cast<float4*>(a.ef + j) = make_float4(e[0], e[1], e[2], e[3]);
+      *reinterpret_cast<float4*>(a.ef + j + 4) = make_float4(e[4], e[5], e[6], e[7]);
+    }
+  }
+}
+
+// Alg. 1's estimate without rotation: out = m + X (M-m)/(g n), sixteen coordinates per thread.
+struct UDequantArgs {
+  const void* agg;
+  const float* range_M;
+  const float* range_m;
+  float* out;
+  uint64_t d;
+  uint32_t L, agg_bits, divisor;
+};
+
+__global__ __launch_bounds__(256) void k_uniform_dequant(const UDequantArgs a) {
+  const uint64_t j = ((uint64_t)blockIdx.x * 256 + threadIdx.x) * 16;
+  if (j >= a.d) return;
+  uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0}, y[16];
+  codes_load(static_cast<const uint8_t*>(a.agg), a.agg_bits, j, w, y);
+  codes_decode(a.agg_bits, true, w, y);
+  const uint64_t blk = j >> a.L;
+  const float M = a.range_M[blk], m = lower_of(a.range_m, blk, M);
+  const float step = (float)(((double)M - (double)m) / (double)a.divisor);
+  float v[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) v[e] = (float)y[e] * step + m;
+#pragma unroll
+  for (int e = 0; e < 16; e += 4)
+    *reinterpret_cast<float4*>(a.out + j + e) = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -1,0 +1,88 @@
+"""Uniform THC (Alg. 1) on the GPU library against the oracle: global min/max ranges, uniform stochastic
+quantization with and without the rotation, error feedback, the estimate of the mean."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import thc_oracle as o
+from paper_2302_08545_amd import api
+from tests.test_gpu_parity import DEV, SEED, assert_indices_match, make_grads, rel_l2, to_np32
+
+pytestmark = pytest.mark.gpu
+F32 = np.float32
+
+
+def uparams(d, block, n, b, agg_bits, bf16=False):
+    T = list(range(2 ** b))
+    P = o.Params(d=d, block=block, n=n, b=b, g=2 ** b - 1, t_p=1.0, seed=SEED, table=T, agg_bits=agg_bits)
+    L = api.make_params(d, block, n, b, 2 ** b - 1, 1.0, SEED, T, agg_bits,
+                        api.THC_DTYPE_BF16 if bf16 else api.THC_DTYPE_F32)
+    return P, L
+
+
+@pytest.mark.parametrize("rotate", [False, True], ids=["plain", "rotated"])
+@pytest.mark.parametrize("block,K,n,b,agg_bits,ef", [(1 << 10, 5, 3, 4, 8, False), (1 << 12, 2, 4, 2, 4, True),
+                                                     (1 << 14, 2, 8, 4, 7, False), (1 << 16, 1, 2, 8, 9, True),
+                                                     (1 << 20, 1, 3, 1, 2, False), (1 << 21, 1, 2, 3, 4, True)])
+def test_uniform_round(block, K, n, b, agg_bits, ef, rotate):
+    d = block * K
+    P, L = uparams(d, block, n, b, agg_bits)
+    grads = make_grads(d, n, seed=block % 97 + b)
+    for i, g in enumerate(grads):
+        g += 0.002 * (i - 1)                                      # asymmetric ranges: m != -M
+    dg = [g.to(DEV) for g in grads]
+    gn = [to_np32(g) for g in grads]
+    gen = torch.Generator().manual_seed(5)
+    efs0 = [(torch.randn(d, generator=gen) * 2e-4).numpy() for _ in range(n)] if ef else None
+    defs = [torch.from_numpy(e).to(DEV) for e in efs0] if ef else None
+    ws = torch.empty(api.thc_workspace_bytes(L), dtype=torch.uint8, device=DEV)
+    rm = torch.zeros(K, dtype=torch.float32, device=DEV)
+    rM = torch.zeros(K, dtype=torch.float32, device=DEV)
+    packed = [torch.zeros(d * b // 8, dtype=torch.uint8, device=DEV) for _ in range(n)]
+    agg = torch.zeros(d * agg_bits // 8, dtype=torch.uint8, device=DEV)
+    out = torch.zeros(d, dtype=torch.float32, device=DEV)
+    rnd = 3
+    api.thc_uniform_prepare_range(L, rnd, dg, defs, rotate, rm, rM, ws)
+    m_ref, M_ref = o.uniform_range(P, rnd, gn, efs0, rotate)
+    # minima and maxima are order-independent: the range is bit-exact, rotated or not
+    assert np.array_equal(rm.cpu().numpy(), m_ref) and np.array_equal(rM.cpu().numpy(), M_ref)
+    packed_ref = []
+    for i in range(n):
+        api.thc_uniform_compress(L, i, rnd, dg[i], None if defs is None else defs[i], rotate, rm, rM, packed[i], ws)
+        pk, ne = o.uniform_compress(P, i, rnd, gn[i], None if efs0 is None else efs0[i], m_ref, M_ref, rotate)
+        assert_indices_match(packed[i].cpu().numpy(), pk, b, f"worker {i}")
+        packed_ref.append(pk)
+        if ef:
+            assert rel_l2(defs[i].cpu().numpy(), ne) <= 1e-5
+    api.thc_aggregate(L, packed, agg)
+    Y = o.aggregate(P, packed_ref)
+    assert np.array_equal(agg.cpu().numpy(), o.aggregate_stream(P, Y))
+    api.thc_uniform_decompress(L, rnd, agg, rotate, rm, rM, out, ws)
+    ref = o.uniform_decompress(P, rnd, Y, m_ref, M_ref, rotate)
+    assert rel_l2(out.cpu().numpy(), ref) <= 1e-5
+
+
+def test_uniform_needs_the_identity_table():
+    L = api.make_params(1 << 12, 1 << 12, 2, 2, 8, 1.0, SEED, [0, 3, 5, 8], 8)
+    z = torch.zeros(16, dtype=torch.float32, device=DEV)
+    with pytest.raises(api.ThcError) as e:
+        api.thc_uniform_decompress(L, 0, z, False, z, z, z, z)
+    assert e.value.status == -2
+
+
+def test_bf16_uniform_plain():
+    d, block, n, b = 1 << 13, 1 << 12, 2, 4
+    P, L = uparams(d, block, n, b, 8, bf16=True)
+    grads = make_grads(d, n, seed=4, bf16=True)
+    dg = [g.to(DEV) for g in grads]
+    gn = [to_np32(g) for g in grads]
+    ws = torch.empty(api.thc_workspace_bytes(L), dtype=torch.uint8, device=DEV)
+    rm = torch.zeros(2, dtype=torch.float32, device=DEV)
+    rM = torch.zeros(2, dtype=torch.float32, device=DEV)
+    api.thc_uniform_prepare_range(L, 0, dg, None, False, rm, rM, ws)
+    m_ref, M_ref = o.uniform_range(P, 0, gn, None, False)
+    assert np.array_equal(rm.cpu().numpy(), m_ref) and np.array_equal(rM.cpu().numpy(), M_ref)
+    pk = torch.zeros(d * b // 8, dtype=torch.uint8, device=DEV)
+    api.thc_uniform_compress(L, 1, 0, dg[1], None, False, rm, rM, pk, None)
+    ref, _ = o.uniform_compress(P, 1, 0, gn[1], None, m_ref, M_ref, False)
+    assert_indices_match(pk.cpu().numpy(), ref, b)
