@@ -14,7 +14,7 @@ THC_DTYPE_F32, THC_DTYPE_BF16 = 0, 1
 
 EXPORTS = ("thc_version", "thc_strerror", "thc_workspace_bytes", "thc_prepare_range", "thc_compress",
            "thc_aggregate", "thc_decompress", "thc_uniform_prepare_range", "thc_uniform_compress",
-           "thc_uniform_decompress", "thc_threshold", "thc_solve_table")
+           "thc_uniform_decompress", "thc_threshold", "thc_solve_table", "thc_solve_table_bruteforce")
 
 
 class thc_params(C.Structure):
@@ -53,6 +53,8 @@ def lib():
         L.thc_threshold.restype = C.c_double
         L.thc_threshold.argtypes = [C.c_double]
         L.thc_solve_table.argtypes = [u32, u32, C.c_double, C.POINTER(C.c_uint8), C.POINTER(C.c_double)]
+        L.thc_solve_table_bruteforce.argtypes = [u32, u32, C.c_double, C.POINTER(C.c_uint8), C.POINTER(C.c_double),
+                                                 C.POINTER(C.c_uint64)]
         _LIB = L
     return _LIB
 
@@ -156,3 +158,12 @@ def thc_solve_table(b: int, g: int, p: float):
     cost = C.c_double(0.0)
     _check(lib().thc_solve_table(b, g, p, out, C.byref(cost)), "thc_solve_table")
     return [int(out[i]) for i in range(2 ** b)], cost.value
+
+
+def thc_solve_table_bruteforce(b: int, g: int, p: float):
+    """Exhaustive search over Alg. 4's enumeration.  Returns (table, cost, number of candidates visited)."""
+    out = (C.c_uint8 * 256)()
+    cost = C.c_double(0.0)
+    count = C.c_uint64(0)
+    _check(lib().thc_solve_table_bruteforce(b, g, p, out, C.byref(cost), C.byref(count)), "thc_solve_table_bruteforce")
+    return [int(out[i]) for i in range(2 ** b)], cost.value, count.value

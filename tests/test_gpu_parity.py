@@ -467,3 +467,42 @@ def test_workload_c4_shape_first_blocks(w):
 def test_workload_c5_shape_first_block():
     # GPT-2-XL shape: bf16 gradients, Student-t tails, 2^22 blocks, error feedback; 3 of the 32 workers
     _round_vs_oracle(wl.shrink(wl.C5, 1, n=3), rnd=0, rounds=2)
+
+
+# ----------------------------------------------------------------------------- partial aggregation (Sec. 6)
+def test_partial_aggregation_with_exact_width_sums():
+    """The PS may aggregate only the workers that answered in time (Sec. 6; 90 % suffices in Sec. 8.4): the sum runs over a
+    subset, the workers divide by its size, and ceil(log2(g m + 1)) bits per sum are enough (Sec. 8.4)."""
+    import math
+    block, K, n = 1 << 13, 3, 8
+    d = block * K
+    P, L = both_params(d, block, n)
+    grads = make_grads(d, n, seed=23)
+    R = GpuRound(L)
+    dg = [x.to(DEV) for x in grads]
+    R.prepare(7, dg)
+    R.compress_all(7, dg)
+    M = R.range_M.cpu().numpy()
+    subset = [0, 2, 3, 5, 6, 7]                                   # two stragglers left out
+    m = len(subset)
+    w = math.ceil(math.log2(30 * m + 1))                          # 8 bits for 181 values
+    Pm, Lm = both_params(d, block, m, agg_bits=w)
+    agg = torch.zeros(d * w // 8, dtype=torch.uint8, device=DEV)
+    out = torch.zeros(d, dtype=torch.float32, device=DEV)
+    api.thc_aggregate(Lm, [R.packed[i] for i in subset], agg)
+    Y = o.aggregate(Pm, [R.packed[i].cpu().numpy() for i in subset])
+    assert np.array_equal(agg.cpu().numpy(), o.aggregate_stream(Pm, Y))
+    api.thc_decompress(Lm, 7, agg, R.range_M, out, R.ws)
+    ref = o.decompress(Pm, 7, Y, M)
+    assert rel_l2(out.cpu().numpy(), ref) <= 1e-5
+    # the estimate is of the subset's mean (the range of all eight workers still bounds it)
+    mean_sub = np.mean([to_np32(grads[i]).astype(np.float64) for i in subset], axis=0)
+    assert o.nmse(mean_sub, out.cpu().numpy()) < 0.03
+    # a narrower sum: 4 of 8 workers need only 7 bits
+    P4, L4 = both_params(d, block, 4, agg_bits=7)
+    agg7 = torch.zeros(d * 7 // 8, dtype=torch.uint8, device=DEV)
+    api.thc_aggregate(L4, R.packed[:4], agg7)
+    Y4 = o.aggregate(P4, [R.packed[i].cpu().numpy() for i in range(4)])
+    assert np.array_equal(agg7.cpu().numpy(), o.aggregate_stream(P4, Y4))
+    api.thc_decompress(L4, 7, agg7, R.range_M, out, R.ws)
+    assert rel_l2(out.cpu().numpy(), o.decompress(P4, 7, Y4, M)) <= 1e-5

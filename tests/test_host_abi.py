@@ -148,3 +148,40 @@ def test_workload_recipes_on_cpu():
     assert 0.5e-4 < sig < 2e-2 and 0.0005 < float((c4.abs() > 40 * sig).float().mean()) < 0.002
     c2 = wl.gradient(wl.shrink(wl.C2, 1, n=1), 0)
     assert int((c2[wl.C2.real:] != 0).sum()) == 0 and int((c2[:wl.C2.real] != 0).sum()) > 0.99 * wl.C2.real
+
+
+# ----------------------------------------------------------------------------- table tool (App. B)
+@pytest.mark.parametrize("b,g", [(1, 1), (1, 7), (2, 3), (2, 4), (2, 9), (2, 16), (2, 30), (3, 7), (3, 8), (3, 13), (3, 18),
+                                 (3, 21), (4, 15), (4, 16), (4, 19), (4, 22)])
+def test_exhaustive_search_agrees_with_the_shortest_path_solver(b, g):
+    for p in (1 / 32, 1 / 1024):
+        tb, cb, cnt = api.thc_solve_table_bruteforce(b, g, p)
+        td, cd = api.thc_solve_table(b, g, p)
+        assert cnt == math.comb(g - 1, 2 ** b - 2)         # strictly increasing tables from 0 to g
+        assert tb == td and cb == pytest.approx(cd, rel=1e-12)
+        assert tb == o.solve_table(b, g, p)
+
+
+def test_exhaustive_search_refuses_hopeless_sizes():
+    import ctypes as C
+    out = (C.c_uint8 * 256)()
+    assert api.lib().thc_solve_table_bruteforce(4, 51, 1 / 32, out, None, None) == -4    # C(50, 14) ~ 9.4e11 candidates
+    assert math.comb(50, 14) > 4e9
+
+
+def test_all_tables_the_paper_mentions_within_seconds():
+    import time
+    from paper_2302_08545_amd import tables
+    t0 = time.perf_counter()
+    all_t = tables.solve_all()
+    dt = time.perf_counter() - t0
+    assert len(all_t) == sum(51 - (2 ** b - 1) + 1 for b in (1, 2, 3, 4)) * len(tables.P_VALUES)
+    assert dt < 60                                         # App. B: thousands of tables "within mere minutes"
+    for (b, g, p), (t, c) in all_t.items():
+        assert t[0] == 0 and t[-1] == g and all(x < y for x, y in zip(t, t[1:]))
+    # cost falls with the bit budget and, at fixed b, a grid that refines another is never worse
+    for p in tables.P_VALUES:
+        assert all_t[(2, 24, p)][1] > all_t[(3, 24, p)][1] > all_t[(4, 24, p)][1]
+        for b in (2, 3, 4):
+            for g in range(2 ** b - 1, 26):
+                assert all_t[(b, 2 * g, p)][1] <= all_t[(b, g, p)][1] * (1 + 1e-12)
