@@ -26,7 +26,7 @@ HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E
 MEASURED_TRAFFIC_BYTES = {"c3_vgg16": (4194378.8 * 2.0 + 8397600.4 * 1.0) * 1024.0}
 
 
-def cpu_baseline(w, table, t_p, seed, budget_blocks=8):
+def cpu_baseline(w, table, t_p, seed, order=0, budget_blocks=8):
     """The oracle as it stands, timed on the host on a bounded sample: the first block(s) of the same
     workload, all n workers, one full round."""
     import numpy as np
@@ -35,7 +35,8 @@ def cpu_baseline(w, table, t_p, seed, budget_blocks=8):
     ws = wl.shrink(w, budget_blocks)
     grads = [wl.gradient(ws, i, device="cpu").to(dtype=__import__("torch").float32).numpy() for i in range(ws.n)]
     efs = [np.zeros(ws.d, dtype=np.float32) for _ in range(ws.n)] if ws.ef else None
-    P = o.Params(d=ws.d, block=ws.block, n=ws.n, b=ws.b, g=ws.g, t_p=t_p, seed=seed, table=table, agg_bits=ws.agg_bits)
+    P = o.Params(d=ws.d, block=ws.block, n=ws.n, b=ws.b, g=ws.g, t_p=t_p, seed=seed, table=table, agg_bits=ws.agg_bits,
+                 order=order)
     t0 = time.perf_counter()
     o.thc_round(P, 0, grads, efs)
     dt = time.perf_counter() - t0
@@ -52,6 +53,8 @@ def main():
     ap.add_argument("--workload", default="c3_vgg16")
     ap.add_argument("--blocks", type=int, default=0, help="use only the first N RHT blocks (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stage-order", choices=("ascending", "split"), default="split",
+                    help="order of the butterfly stages (thc_params.stage_order)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device-to-device copy five times and exit (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -80,8 +83,9 @@ def main():
         w = wl.shrink(w, args.blocks)
     table, t_p = wl.table_and_threshold(w)
     seed = wl.RHT_SEED
+    order = api.THC_ORDER_SPLIT if args.stage_order == "split" else api.THC_ORDER_ASCENDING
     L = api.make_params(w.d, w.block, w.n, w.b, w.g, t_p, seed, table, w.agg_bits,
-                        api.THC_DTYPE_BF16 if w.dtype == "bf16" else api.THC_DTYPE_F32)
+                        api.THC_DTYPE_BF16 if w.dtype == "bf16" else api.THC_DTYPE_F32, order)
 
     grads = [wl.gradient(w, i, device=dev) for i in range(w.n)]
     efs = [torch.zeros(w.d, dtype=torch.float32, device=dev) for _ in range(w.n)] if w.ef else None
@@ -147,7 +151,8 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "d_padded": w.d, "d_real": w.real, "rht_block": w.block, "workers": w.n,
-                   "b": w.b, "g": w.g, "agg_bits": w.agg_bits, "error_feedback": w.ef, "input": w.dtype},
+                   "b": w.b, "g": w.g, "agg_bits": w.agg_bits, "error_feedback": w.ef, "input": w.dtype,
+                   "stage_order": args.stage_order},
         "worker_coords_per_s": w.n * w.d / (dt / args.steps),
         "effective_hbm_GBps": bpc * w.d / (dt / args.steps) / 1e9,
         "effective_hbm_frac": bpc * w.d / (dt / args.steps) / 1e9 / HBM_PEAK_GBPS,
@@ -158,7 +163,7 @@ def main():
                      "algorithmic_bytes": lo_alg_bytes, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, table, t_p, seed)
+        result["cpu_baseline"] = cpu_baseline(w, table, t_p, seed, order)
     print(json.dumps(result), flush=True)
 
 

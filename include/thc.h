@@ -33,8 +33,8 @@
  *     (j mod 32) of word ((j div 32) mod 4) of Philox(counter (q, q>>32, round, 0x80000000)), q = j div 128.
  *     Rounding draw of worker i: coordinate j takes 16-bit half (j mod 8) (low half first) of
  *     Philox(counter (q, q>>32, round, i)), q = j div 8; u = (half + 1/2) / 2^16.
- *   - Butterflies of the Hadamard transform run in ascending stride order in binary32 without fused
- *     multiply-add; packed bytes and aggregated sums are therefore reproducible bit for bit.
+ *   - Butterflies of the Hadamard transform run in the stage order of thc_params.stage_order, in binary32,
+ *     without fused multiply-add; packed bytes and aggregated sums are therefore reproducible bit for bit.
  */
 #ifndef THC_H_
 #define THC_H_
@@ -58,6 +58,14 @@ typedef enum thc_status {
 enum { THC_MAX_WORKERS = 64 };
 enum { THC_DTYPE_F32 = 0, THC_DTYPE_BF16 = 1 };
 
+/* Order in which the butterfly stages of the Hadamard transform run (each stage pairs coordinates whose
+ * offsets inside the block differ in one bit).  Every order computes the same transform; in binary32 the
+ * roundings differ, so the order is part of what makes results reproducible bit for bit.
+ *   THC_ORDER_ASCENDING  bits 0, 1, ..., log2(B)-1.
+ *   THC_ORDER_SPLIT      for B >= 2^16: bits 0..9, 13, 14, 15, then 10, 11, 12, 16, ..., log2(B)-1 (the memory
+ *                        access pattern of the first pass is faster on MI355X); same as ascending below 2^16. */
+enum { THC_ORDER_ASCENDING = 0, THC_ORDER_SPLIT = 1 };
+
 /* The problem statement of Alg. 3.  Plain data, owned by the caller, read on the host only. */
 typedef struct thc_params {
   uint64_t d;          /* padded coordinate count per worker; a multiple of `block`                        */
@@ -70,6 +78,8 @@ typedef struct thc_params {
   float    t_p;        /* truncation threshold Phi^-1(1 - p/2) (Sec. 5.1); see thc_threshold               */
   uint64_t seed;       /* shared by all workers and the decompressor                                       */
   uint8_t  table[256]; /* T[0 .. 2^b-1]; see thc_solve_table                                               */
+  uint32_t stage_order;/* THC_ORDER_ASCENDING or THC_ORDER_SPLIT                                           */
+  uint32_t reserved;   /* must be 0                                                                        */
 } thc_params;
 
 /* Library version (major*10000 + minor*100 + patch). */

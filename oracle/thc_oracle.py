@@ -162,7 +162,8 @@ class Params:
     t_p: float              # Phi^-1(1 - p/2), stored as binary32
     seed: int               # shared 64-bit seed
     table: Sequence[int]    # T[0..2^b-1], 0 = T[0] < ... < T[2^b-1] = g
-    agg_bits: int = 8       # width of one aggregated value (8 or 16)
+    agg_bits: int = 8       # width of one aggregated value (1..16 bits)
+    order: int = 0          # butterfly stage order, see stage_order()
     F: np.ndarray = field(init=False, repr=False)
 
     def __post_init__(self):
@@ -204,20 +205,35 @@ def fwht_loops(x: Sequence[float]) -> np.ndarray:
     return y
 
 
-def fwht_f32(x: np.ndarray) -> np.ndarray:
-    """Same butterflies as `fwht_loops`, vectorised, along the last axis (binary32)."""
+def stage_order(B: int, order: int = 0) -> List[int]:
+    """The bit positions of the butterfly stages, in processing order (a stage on bit k pairs coordinates
+    whose offsets in the block differ by 2^k).  order 0: ascending, 0, 1, ..., log2(B)-1.  order 1 ("split"),
+    for B >= 2^16: 0..9, 13, 14, 15, then 10, 11, 12, 16, ..., log2(B)-1; ascending for smaller blocks.
+    Any order computes H x exactly in exact arithmetic; binary32 roundings depend on it."""
+    L = B.bit_length() - 1
+    if order == 1 and L >= 16:
+        return list(range(10)) + [13, 14, 15, 10, 11, 12] + list(range(16, L))
+    return list(range(L))
+
+
+def fwht_f32(x: np.ndarray, bits: Optional[Sequence[int]] = None) -> np.ndarray:
+    """Same butterflies as `fwht_loops`, vectorised, along the last axis (binary32); `bits` lists the
+    stages (bit positions) in processing order, ascending by default."""
     y = np.array(x, dtype=F32, copy=True)
     B = y.shape[-1]
     assert B & (B - 1) == 0
+    L = B.bit_length() - 1
+    if bits is None:
+        bits = range(L)
+    assert sorted(bits) == list(range(L))
     lead = y.shape[:-1]
-    h = 1
-    while h < B:
+    for k in bits:
+        h = 1 << k
         v = y.reshape(lead + (B // (2 * h), 2, h))
         a = v[..., 0, :].copy()
         b = v[..., 1, :].copy()
         v[..., 0, :] = a + b
         v[..., 1, :] = a - b
-        h *= 2
     return y
 
 
@@ -226,15 +242,15 @@ def rht_scale(B: int) -> np.float32:
     return F32(1.0 / math.sqrt(float(B)))
 
 
-def rht_blocks(x: np.ndarray, signs: np.ndarray, B: int) -> np.ndarray:
+def rht_blocks(x: np.ndarray, signs: np.ndarray, B: int, order: int = 0) -> np.ndarray:
     """RHT(x) = (1/sqrt(B)) H D x on every block of B coordinates (Sec. 5.1)."""
     v = (x.astype(F32) * signs).reshape(-1, B)
-    return (fwht_f32(v) * rht_scale(B)).astype(F32).reshape(-1)
+    return (fwht_f32(v, stage_order(B, order)) * rht_scale(B)).astype(F32).reshape(-1)
 
 
-def irht_blocks(v: np.ndarray, signs: np.ndarray, B: int) -> np.ndarray:
+def irht_blocks(v: np.ndarray, signs: np.ndarray, B: int, order: int = 0) -> np.ndarray:
     """RHT^-1(v) = (1/sqrt(B)) D H v on every block (Sec. 5.1)."""
-    h = fwht_f32(v.astype(F32).reshape(-1, B)).reshape(-1)
+    h = fwht_f32(v.astype(F32).reshape(-1, B), stage_order(B, order)).reshape(-1)
     return ((h * rht_scale(B)).astype(F32) * signs).astype(F32)
 
 
@@ -369,14 +385,14 @@ def compress(P: Params, worker: int, rnd: int, grad: np.ndarray, ef: Optional[np
     assert d == P.d
     x = ef_input(grad, ef)
     signs = rademacher_signs(P.seed, rnd, j0, d)
-    R = rht_blocks(x, signs, P.block)
+    R = rht_blocks(x, signs, P.block, P.order)
     h16 = sq_halfwords(P.seed, rnd, worker, j0, d)
     z = quantize_rotated(P, R, range_M, h16)
     packed = pack_indices(z, P.b)
     new_ef = None
     if ef is not None:
         X = dequantize_indices(P, z, range_M)
-        new_ef = (x - irht_blocks(X, signs, P.block)).astype(F32)
+        new_ef = (x - irht_blocks(X, signs, P.block, P.order)).astype(F32)
     return packed, new_ef
 
 
@@ -407,7 +423,7 @@ def decompress(P: Params, rnd: int, Y: np.ndarray, range_M: np.ndarray, j0: int 
     M = np.repeat(range_M.astype(F32), P.block)
     v = ((Y.astype(F32) * sn).astype(F32) + (-M)).astype(F32)
     signs = rademacher_signs(P.seed, rnd, j0, P.d)
-    return irht_blocks(v, signs, P.block)
+    return irht_blocks(v, signs, P.block, P.order)
 
 
 # --------------------------------------------------------------------------- #
@@ -418,7 +434,7 @@ def uniform_values(P: Params, rnd: int, grad: np.ndarray, ef: Optional[np.ndarra
     """What a worker quantizes: x = grad + e, rotated block-wise when `rotate`."""
     x = ef_input(grad, ef)
     if rotate:
-        x = rht_blocks(x, rademacher_signs(P.seed, rnd, 0, P.d), P.block)
+        x = rht_blocks(x, rademacher_signs(P.seed, rnd, 0, P.d), P.block, P.order)
     return x
 
 
@@ -446,7 +462,7 @@ def uniform_compress(P: Params, worker: int, rnd: int, grad: np.ndarray, ef: Opt
     if ef is not None:
         X = dequantize_indices(P, z, range_M, range_m)
         if rotate:
-            X = irht_blocks(X, rademacher_signs(P.seed, rnd, 0, P.d), P.block)
+            X = irht_blocks(X, rademacher_signs(P.seed, rnd, 0, P.d), P.block, P.order)
         new_ef = (x - X).astype(F32)
     return pack_indices(z, P.b), new_ef
 
@@ -457,7 +473,7 @@ def uniform_decompress(P: Params, rnd: int, Y: np.ndarray, range_m: np.ndarray, 
     _, _, step_n = block_scalars(P, range_M, range_m)
     v = ((Y.astype(F32) * np.repeat(step_n, P.block)).astype(F32) + np.repeat(range_m.astype(F32), P.block)).astype(F32)
     if rotate:
-        v = irht_blocks(v, rademacher_signs(P.seed, rnd, 0, P.d), P.block)
+        v = irht_blocks(v, rademacher_signs(P.seed, rnd, 0, P.d), P.block, P.order)
     return v
 
 

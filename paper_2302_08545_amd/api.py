@@ -11,6 +11,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libthc.so")
 
 THC_MAX_WORKERS = 64
 THC_DTYPE_F32, THC_DTYPE_BF16 = 0, 1
+THC_ORDER_ASCENDING, THC_ORDER_SPLIT = 0, 1
 
 EXPORTS = ("thc_version", "thc_strerror", "thc_workspace_bytes", "thc_prepare_range", "thc_compress",
            "thc_aggregate", "thc_decompress", "thc_uniform_prepare_range", "thc_uniform_compress",
@@ -20,7 +21,8 @@ EXPORTS = ("thc_version", "thc_strerror", "thc_workspace_bytes", "thc_prepare_ra
 class thc_params(C.Structure):
     _fields_ = [("d", C.c_uint64), ("block", C.c_uint64), ("n", C.c_uint32), ("b", C.c_uint32),
                 ("g", C.c_uint32), ("agg_bits", C.c_uint32), ("in_dtype", C.c_uint32), ("t_p", C.c_float),
-                ("seed", C.c_uint64), ("table", C.c_uint8 * 256)]
+                ("seed", C.c_uint64), ("table", C.c_uint8 * 256), ("stage_order", C.c_uint32),
+                ("reserved", C.c_uint32)]
 
 
 class ThcError(RuntimeError):
@@ -60,8 +62,9 @@ def lib():
 
 
 def make_params(d: int, block: int, n: int, b: int, g: int, t_p: float, seed: int, table: Sequence[int],
-                agg_bits: int = 8, in_dtype: int = THC_DTYPE_F32) -> thc_params:
+                agg_bits: int = 8, in_dtype: int = THC_DTYPE_F32, stage_order: int = THC_ORDER_ASCENDING) -> thc_params:
     p = thc_params()
+    p.stage_order = stage_order
     p.d, p.block, p.n, p.b, p.g = d, block, n, b, g
     p.agg_bits, p.in_dtype, p.t_p, p.seed = agg_bits, in_dtype, t_p, seed
     for i, v in enumerate(table):

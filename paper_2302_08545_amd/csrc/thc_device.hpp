@@ -20,6 +20,43 @@ struct PtrArr {
 };
 
 // ---------------------------------------------------------------------------------------------
+// Bit-permuted tiling.  Every transform pass cuts a block of 2^L coordinates into tiles of 8192: a tile is
+// 2^nrows rows of 2^logw consecutive coordinates (nrows + logw = 13).  The offset bits of a coordinate
+// inside its block are dealt out as
+//   bits [0, logw)                          the column inside the row,
+//   [sh0, sh0 + n0) and [sh1, ...)          the row index: its low n0 bits, then the rest,
+//   runs (flen, fpos)                       the bit positions the tile index inside the block is scattered to.
+// The host orders the runs so that the low three bits of the tile index (workgroup ids are dealt round-robin to
+// the 8 XCDs) land on the offset bits that measured fastest for that pass.
+// ---------------------------------------------------------------------------------------------
+struct TileMap {
+  uint8_t L;        // log2 of the span the tile index runs over (the block, or 13 for blocks below 8192)
+  uint8_t logw;
+  uint8_t nrows;
+  uint8_t nfixed;   // = L - 13
+  uint8_t n0, sh0, sh1, pad;
+  // the tile index inside the span, cut into up to four runs of consecutive bits: run i is flen[i] bits long
+  // and lands at offset bit fpos[i] (unused runs have length 0)
+  uint8_t flen[4];
+  uint8_t fpos[4];
+};
+
+__device__ __forceinline__ uint64_t tm_base(const TileMap& m, uint64_t tile) {
+  uint64_t off = (tile >> m.nfixed) << m.L;
+  uint32_t tib = (uint32_t)(tile & ((1ull << m.nfixed) - 1));
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    off |= (uint64_t)(tib & ((1u << m.flen[i]) - 1u)) << m.fpos[i];
+    tib >>= m.flen[i];
+  }
+  return off;
+}
+
+__device__ __forceinline__ uint32_t tm_row(const TileMap& m, uint32_t r) {
+  return ((r & ((1u << m.n0) - 1u)) << m.sh0) | ((r >> m.n0) << m.sh1);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11).  One call yields 128 bits.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
@@ -101,7 +138,8 @@ __device__ __forceinline__ int phys(int i) {
 }
 
 // One round: every thread gathers 16 values as (16 >> NB) groups of 2^NB values that differ in index
-// bits [P, P+NB), runs the butterflies, and hands each result to sink(index, value).
+// bits [P, P+NB), runs the butterflies, and hands each result to sink(base, e << P, value): the value's
+// tile index is base + (e << P), the two parts have no bits in common and the second is a constant.
 template <int P, int NB, Layout LY, class Sink>
 __device__ __forceinline__ void lds_round(const float* lds, int t, Sink&& sink) {
   constexpr int E = 1 << NB;
@@ -119,7 +157,7 @@ __device__ __forceinline__ void lds_round(const float* lds, int t, Sink&& sink) 
     for (int e = 0; e < E; ++e) v[e] = (LY == SWZ) ? lds[swz(base + (e << P))] : pb[e * ESTR];
     bfly<NB>(v);
 #pragma unroll
-    for (int e = 0; e < E; ++e) sink(base + (e << P), v[e]);
+    for (int e = 0; e < E; ++e) sink(base, e << P, v[e]);
   }
 }
 
@@ -134,7 +172,7 @@ __device__ __forceinline__ void lds_stages(float* lds, int t, Sink&& sink) {
     lds_round<P, NB, LY>(lds, t, sink);
   } else {
     if constexpr (NB > 0) {
-      lds_round<P, NB, LY>(lds, t, [&](int i, float v) { lds[phys<LY>(i)] = v; });
+      lds_round<P, NB, LY>(lds, t, [&](int base, int eoff, float v) { lds[phys<LY>(base + eoff)] = v; });
     }
     if constexpr (!LAST) lds_stages<P + NB, HI, FUSE, LY>(lds, t, sink);
   }

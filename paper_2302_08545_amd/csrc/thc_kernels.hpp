@@ -24,7 +24,16 @@ struct FwdLoArgs {
   double* partials;    // n * (d >> min(L, 13)) doubles
   uint64_t d;
   uint32_t round, k0, k1;
+  TileMap tm;          // only `fixed` is used: the tile shape is a template parameter
 };
+
+// Tile index -> offset inside the tile's span for the "lo" passes.  XO = false: 8192 consecutive
+// coordinates.  XO = true: eight rows of 1024 consecutive coordinates, rows at offset bits 13..15 (the
+// workgroup's XCD then stays on one value of offset bits 10..12 for reads and writes alike).
+template <bool XO>
+__device__ __forceinline__ uint32_t lo_map(uint32_t idx) {
+  return XO ? ((idx & 1023u) | ((idx >> 10) << 13)) : idx;
+}
 
 template <bool BF16>
 __device__ __forceinline__ float4 load_grad4(const void* g, uint64_t j) {
@@ -38,8 +47,9 @@ __device__ __forceinline__ float4 load_grad4(const void* g, uint64_t j) {
 
 // One workgroup per tile (grid = (tiles, n workers)): measured on MI355X this streams faster than a
 // persistent grid with software prefetch, the hardware dispatcher keeps four workgroups per CU in flight.
-template <int L1, bool BF16, bool EF>
+template <int L1, bool BF16, bool EF, bool XO>
 __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
+  static_assert(!XO || L1 == LOG_TILE, "the row-split tile needs blocks of at least 2^16");
   // Vectors are multiples of B, so only blocks shorter than a tile can leave the last tile partial.
   constexpr bool GUARD = L1 < LOG_TILE;
   __shared__ __align__(16) float lds[TILE_PAD];
@@ -51,13 +61,13 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
   const void* grad = a.grads.p[worker];
   const float* ef = EF ? static_cast<const float*>(a.efs.p[worker]) : nullptr;
   const int wave = t >> 6, lane = t & 63;
-  const uint64_t off = (uint64_t)blockIdx.x << LOG_TILE;
+  const uint64_t off = tm_base(a.tm, blockIdx.x);   // coordinate of tile index 0
 
   // all loads of the tile are issued before anything waits on them
   float4 x[4], e[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const uint64_t j = off + 4u * (uint32_t)(i * NT + t);
+    const uint64_t j = off + lo_map<XO>(4u * (uint32_t)(i * NT + t));
     const bool ok = !GUARD || j < a.d;
     x[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     e[i] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -68,7 +78,7 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
   }
 
   if (t < 64) {   // the tile's 8192 diagonal entries: 64 Philox calls of 128 bits
-    const uint64_t q = (off >> 7) + t;
+    const uint64_t q = (off + lo_map<XO>(128u * t)) >> 7;
     const uint4 r = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, SIGN_STREAM, a.k0, a.k1);
     *reinterpret_cast<uint4*>(&sgn[4 * t]) = r;
   }
@@ -113,7 +123,8 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
 #pragma unroll
       for (int w = 0; w < 4; ++w) s += wsum[t >> 1][4 * (t & 1) + w];
     }
-    const uint64_t pidx = (off >> L1) + t;
+    // one partial per tile (all of it in one block) or, for blocks below 8192, per block of the linear tile
+    const uint64_t pidx = L1 >= LOG_TILE ? (uint64_t)blockIdx.x : (off >> L1) + t;
     if (pidx < (a.d >> L1)) a.partials[(uint64_t)worker * (a.d >> L1) + pidx] = s;
   }
 
@@ -132,8 +143,8 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
 
   float* dst = a.ws_x + (uint64_t)worker * a.d + off;
   const uint64_t left = a.d - off;   // coordinates of this tile that exist (tail tile of a short vector)
-  lds_stages<2, L1, true, PAD>(lds, t, [&](int i, float v) {
-    if (!GUARD || (uint64_t)i < left) dst[i] = v;
+  lds_stages<2, L1, true, PAD>(lds, t, [&](int base, int eoff, float v) {
+    if (!GUARD || (uint64_t)(base + eoff) < left) dst[lo_map<XO>(base) + lo_map<XO>(eoff)] = v;
   });
 }
 
@@ -168,33 +179,19 @@ __global__ __launch_bounds__(64) void k_range(const RangeArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Shared addressing of the strided passes.  A tile is 2^R rows by W = 8192 >> R columns; rows are
-// 2^S0 coordinates apart; 2^(S0+R-13) tiles side by side cover one span of 2^(S0+R) coordinates.
+// Shared addressing of the strided passes: a tile of 2^R rows by W = 8192 >> R columns (see TileMap).
 // ---------------------------------------------------------------------------------------------
 template <int R>
 struct HiGeom {
   static constexpr int LOGW = LOG_TILE - R;
   static constexpr int W = 1 << LOGW;
+  const TileMap& m;
   uint64_t base;   // coordinate of (row 0, col 0)
-  int s0;
-  // Workgroup ids are dealt round-robin to the 8 XCDs.  Measured on MI355X, strided 256-byte row reads run
-  // ~30 % faster when an XCD keeps to columns whose byte offset has the same bits [12,15), so the low three
-  // bits of the id choose the 4 KB column group and the other bits the slot inside it (a bit permutation of
-  // the column-tile index: every tile is still visited exactly once).
-  __device__ HiGeom(uint64_t tile, int s0_) : s0(s0_) {
-    const int lt = s0_ + R - LOG_TILE;                  // log2(tiles per span), >= 0
-    const uint64_t span = tile >> lt;
-    uint32_t ct = (uint32_t)(tile & ((1ull << lt) - 1));
-    constexpr int PER4K = 10 - LOGW;                    // log2(column tiles per 4 KB of columns)
-    if (PER4K >= 0 && lt >= PER4K + 3) {
-      const uint32_t k = ct & 7u, m = ct >> 3;
-      ct = ((((m >> PER4K) << 3) | k) << PER4K) | (m & ((1u << PER4K) - 1u));
-    }
-    base = (span << (s0_ + R)) + (uint64_t)ct * W;
-  }
-  __device__ uint64_t coord(int idx) const {
-    return base + ((uint64_t)(idx >> LOGW) << s0) + (uint32_t)(idx & (W - 1));
-  }
+  __device__ HiGeom(uint64_t tile, const TileMap& m_) : m(m_), base(tm_base(m_, tile)) {}
+  // offset of a tile index from `base`: 32 bits are enough (blocks are at most 2^27 coordinates), so device
+  // addresses can be formed as uniform 64-bit base + 32-bit per-lane offset
+  __device__ uint32_t off(int idx) const { return tm_row(m, (uint32_t)idx >> LOGW) + (uint32_t)(idx & (W - 1)); }
+  __device__ uint64_t coord(int idx) const { return base + off(idx); }
 };
 
 // Front half of a strided pass with R >= 2 row bits (no bounds checks: such tiles are always whole).
@@ -214,12 +211,13 @@ template <int R>
 __device__ __forceinline__ void hi_issue_loads(const float* src, const HiGeom<R>& g, int t, float4 (&x)[4]) {
   using S = HiSplit<R>;
   const int cg = t & (S::W / 4 - 1), rho = t >> (S::LOGW - 2);
-  const float* p = src + g.base + ((uint64_t)(4 * rho) << g.s0) + 4 * cg;
-  const uint64_t pitch = 1ull << g.s0;
-  x[0] = *reinterpret_cast<const float4*>(p);
-  x[1] = *reinterpret_cast<const float4*>(p + pitch);
-  x[2] = *reinterpret_cast<const float4*>(p + 2 * pitch);
-  x[3] = *reinterpret_cast<const float4*>(p + 3 * pitch);
+  const float* pb = src + g.base;
+  const uint32_t o = tm_row(g.m, 4 * rho) + 4 * cg;
+  const uint32_t p1 = tm_row(g.m, 1), p2 = tm_row(g.m, 2);   // rows 4 rho + {1, 2, 3}
+  x[0] = *reinterpret_cast<const float4*>(pb + o);
+  x[1] = *reinterpret_cast<const float4*>(pb + (o + p1));
+  x[2] = *reinterpret_cast<const float4*>(pb + (o + p2));
+  x[3] = *reinterpret_cast<const float4*>(pb + (o + p1 + p2));
 }
 
 // row bits 0 and 1 in registers, then the tile goes to LDS (row-major, no padding)
@@ -240,7 +238,7 @@ __device__ __forceinline__ void hi_r0_to_lds(float4 (&x)[4], float* lds, int t) 
 template <int R>
 __device__ __forceinline__ void hi_round1(float* lds, int t) {
   using S = HiSplit<R>;
-  lds_stages<S::LOGW + 2, S::LOGW + 2 + S::NB1, false, PLAIN>(lds, t, [](int, float) {});
+  lds_stages<S::LOGW + 2, S::LOGW + 2 + S::NB1, false, PLAIN>(lds, t, [](int, int, float) {});
   __syncthreads();
 }
 
@@ -302,14 +300,14 @@ __device__ __forceinline__ void hi_load_to_lds(const float* src, const HiGeom<R>
 struct MidArgs {
   float* x;   // d floats (one worker's half-rotated vector)
   uint64_t d;
-  int s0;
+  TileMap tm;
 };
 
 template <int R>
 __global__ __launch_bounds__(NT) void k_mid(const MidArgs a) {
   __shared__ __align__(16) float lds[TILE];
   const int t = threadIdx.x;
-  const HiGeom<R> g(blockIdx.x, a.s0);
+  const HiGeom<R> g(blockIdx.x, a.tm);
   if constexpr (R >= 2) {
     hi_front<R>(a.x, g, lds, t);
     int idx[2];
@@ -323,7 +321,7 @@ __global__ __launch_bounds__(NT) void k_mid(const MidArgs a) {
     }
   } else {
     hi_load_to_lds<R>(a.x, g, a.d, lds, t);
-    lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, float) {});
+    lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, int, float) {});
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -351,7 +349,7 @@ struct QuantArgs {
   const float* range_m;    // K floats, or null: m = -M
   uint8_t* packed;         // d*b/8 bytes
   uint64_t d;
-  int s0;                  // log2 of the row pitch
+  TileMap tm;
   uint32_t L;              // log2 B
   uint32_t b, g;
   uint32_t round, worker, k0, k1;
@@ -425,7 +423,7 @@ __device__ __forceinline__ float lower_of(const float* range_m, uint64_t blk, fl
 }
 
 template <int R, bool CFOLD>
-__global__ __launch_bounds__(NT) void k_fwd_hi_quant(const QuantArgs a) {
+__global__ __launch_bounds__(NT, 8) void k_fwd_hi_quant(const QuantArgs a) {
   __shared__ __align__(16) float lds[TILE];
   __shared__ uint2 lut[256];
   __shared__ float sM[8], sLo[8], sScale[8];
@@ -433,7 +431,7 @@ __global__ __launch_bounds__(NT) void k_fwd_hi_quant(const QuantArgs a) {
   const int t = threadIdx.x;
 
   if constexpr (R >= 2) {
-    const HiGeom<R> g(blockIdx.x, a.s0);
+    const HiGeom<R> g(blockIdx.x, a.tm);
     float4 x[4];
     hi_issue_loads<R>(a.x, g, t, x);            // tile loads first: everything below overlaps their latency
     build_quant_lut(a, lut, t);
@@ -451,17 +449,19 @@ __global__ __launch_bounds__(NT) void k_fwd_hi_quant(const QuantArgs a) {
     float v[2][8];
     hi_back<R>(lds, t, idx, v);
     const QuantScalars s{sM[0], sLo[0], sScale[0], a.c};
+    const uint64_t q0 = g.base >> 3;            // tiles start on multiples of 64 coordinates
+    uint8_t* const pk0 = a.packed + (g.base >> 3) * a.b;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const uint64_t j = g.coord(idx[h]);
-      const uint64_t q = j >> 3;
+      const uint32_t o = g.off(idx[h]);
+      const uint64_t q = q0 + (o >> 3);
       const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, a.worker, a.k0, a.k1);
       uint32_t z[8];
       quantize8<CFOLD>(v[h], rnd, s, lut, z);
-      store_packed8(a.packed, j, a.b, z);
+      store_packed8(pk0, o, a.b, z);
     }
   } else {
-    const HiGeom<R> g(blockIdx.x, a.s0);
+    const HiGeom<R> g(blockIdx.x, a.tm);
     build_quant_lut(a, lut, t);
     // per-block scalars; a tile spans more than one block only when B < 8192 (then R == 0)
     const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
@@ -474,7 +474,7 @@ __global__ __launch_bounds__(NT) void k_fwd_hi_quant(const QuantArgs a) {
       sScale[t] = scale16_of(M, m, a.g);
     }
     hi_load_to_lds<R>(a.x, g, a.d, lds, t);
-    lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, float) {});
+    lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, int, float) {});
     __syncthreads();
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -562,20 +562,22 @@ struct InvLoArgs {
   uint32_t src_bits;       // bits per coordinate in src
   uint32_t use_table;      // 1: src holds table indices; 0: src holds aggregated table values
   uint32_t divisor;        // g*n (aggregated) or g (indices)
+  TileMap tm;
   uint8_t table[256];
 };
 
-template <int L1>
+template <int L1, bool XO>
 __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
+  static_assert(!XO || L1 == LOG_TILE, "the row-split tile needs blocks of at least 2^16");
   constexpr bool GUARD = L1 < LOG_TILE;
   __shared__ __align__(16) float lds[TILE];
   __shared__ float sM[8], sStep[8];
   __shared__ float tabf[256];
 
   const int t = threadIdx.x;
-  const uint64_t off = (uint64_t)blockIdx.x * TILE;
+  const uint64_t off = tm_base(a.tm, blockIdx.x);
   const int idx = 16 * t;
-  const uint64_t j = off + idx;
+  const uint64_t j = off + lo_map<XO>(idx);
   const bool ok = !GUARD || j < a.d;
 
   // raw bits first, so the load is in flight while the block constants are prepared
@@ -610,8 +612,8 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
 
   float* dst = a.ws_x + off;
   const uint64_t left = a.d - off;
-  lds_stages<4, L1, true, SWZ>(lds, t, [&](int i, float val) {
-    if (!GUARD || (uint64_t)i < left) dst[i] = val;
+  lds_stages<4, L1, true, SWZ>(lds, t, [&](int base, int eoff, float val) {
+    if (!GUARD || (uint64_t)(base + eoff) < left) dst[lo_map<XO>(base) + lo_map<XO>(eoff)] = val;
   });
 }
 
@@ -625,7 +627,7 @@ struct InvHiArgs {
   float* out;          // d floats
   const void* grad;    // mode 1 only
   uint64_t d;
-  int s0;
+  TileMap tm;
   uint32_t round, k0, k1;
   uint32_t mode, bf16;
   float c;
@@ -651,7 +653,7 @@ __global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
   __shared__ uint32_t sgn[TILE / 32];
 
   const int t = threadIdx.x;
-  const HiGeom<R> g(blockIdx.x, a.s0);
+  const HiGeom<R> g(blockIdx.x, a.tm);
 
   if constexpr (R >= 2) {
     hi_front<R>(a.x, g, lds, t);
@@ -673,7 +675,7 @@ __global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
   } else {
     if (t < TILE / 32) sgn[t] = sign_word(g.coord(32 * t), a.round, a.k0, a.k1);
     hi_load_to_lds<R>(a.x, g, a.d, lds, t);
-    lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, float) {});
+    lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, int, float) {});
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -787,7 +789,7 @@ struct HiStoreArgs {
   float* pmin;       // this worker's partial minima, d >> L1 floats
   float* pmax;
   uint64_t d;
-  int s0;
+  TileMap tm;
   uint32_t L;
   float c;
 };
@@ -797,7 +799,7 @@ __global__ __launch_bounds__(NT) void k_fwd_hi_store(const HiStoreArgs a) {
   __shared__ __align__(16) float lds[TILE];
   __shared__ float smin[16], smax[16];
   const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
-  const HiGeom<R> g(blockIdx.x, a.s0);
+  const HiGeom<R> g(blockIdx.x, a.tm);
   if constexpr (R >= 2) {
     hi_front<R>(a.x, g, lds, t);
     int idx[2];
@@ -827,7 +829,7 @@ __global__ __launch_bounds__(NT) void k_fwd_hi_store(const HiStoreArgs a) {
     }
   } else {
     hi_load_to_lds<R>(a.x, g, a.d, lds, t);
-    lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, float) {});
+    lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, int, float) {});
     __syncthreads();
     // thread owns tile indices [8(t + 512h), +8): a wave covers 512 consecutive values per h
 #pragma unroll

@@ -33,11 +33,12 @@ def table_for(b, g, p=1 / 32):
     return o.solve_table(b, g, p)
 
 
-def both_params(d, block, n, b=4, g=30, agg_bits=8, p=1 / 32, bf16=False, seed=SEED, table=None):
+def both_params(d, block, n, b=4, g=30, agg_bits=8, p=1 / 32, bf16=False, seed=SEED, table=None, order=0):
     T = table if table is not None else table_for(b, g, p)
     tp = o.t_p_of(p)
-    P = o.Params(d=d, block=block, n=n, b=b, g=g, t_p=tp, seed=seed, table=T, agg_bits=agg_bits)
-    L = api.make_params(d, block, n, b, g, tp, seed, T, agg_bits, api.THC_DTYPE_BF16 if bf16 else api.THC_DTYPE_F32)
+    P = o.Params(d=d, block=block, n=n, b=b, g=g, t_p=tp, seed=seed, table=T, agg_bits=agg_bits, order=order)
+    L = api.make_params(d, block, n, b, g, tp, seed, T, agg_bits, api.THC_DTYPE_BF16 if bf16 else api.THC_DTYPE_F32,
+                        order)
     return P, L
 
 
@@ -367,8 +368,10 @@ def test_rounds_and_workers_use_different_random_streams_and_calls_are_determini
 
 
 # ----------------------------------------------------------------------------- the bench configuration
-def test_vgg16_shape_full_size_sampled_blocks():
-    """The 138M-coordinate / 2^28-padded, 8-worker, b=4 configuration in the launch shape bench.py times.
+@pytest.mark.parametrize("order", [1, 0], ids=["split-order", "ascending-order"])
+def test_vgg16_shape_full_size_sampled_blocks(order):
+    """The 138M-coordinate / 2^28-padded, 8-worker, b=4 configuration in the launch shape bench.py times
+    (bench.py runs the split stage order by default).
     The oracle checks sampled blocks one by one (blocks are independent THC instances); properties cover
     the rest: zero padding decodes to exactly zero and aggregated sums never exceed g*n."""
     w = wl.C3
@@ -376,8 +379,8 @@ def test_vgg16_shape_full_size_sampled_blocks():
     if free < 30 * (1 << 30):
         pytest.skip("needs ~22 GB of device memory")
     T = o.solve_table(w.b, w.g, w.p)
-    P_blk = o.Params(d=w.block, block=w.block, n=w.n, b=w.b, g=w.g, t_p=o.t_p_of(w.p), seed=SEED, table=T)
-    L = api.make_params(w.d, w.block, w.n, w.b, w.g, o.t_p_of(w.p), SEED, T, w.agg_bits)
+    P_blk = o.Params(d=w.block, block=w.block, n=w.n, b=w.b, g=w.g, t_p=o.t_p_of(w.p), seed=SEED, table=T, order=order)
+    L = api.make_params(w.d, w.block, w.n, w.b, w.g, o.t_p_of(w.p), SEED, T, w.agg_bits, api.THC_DTYPE_F32, order)
     grads = [wl.gradient(w, i, device=DEV) for i in range(w.n)]
     R = GpuRound(L)
     rnd = 5
@@ -506,3 +509,37 @@ def test_partial_aggregation_with_exact_width_sums():
     assert np.array_equal(agg7.cpu().numpy(), o.aggregate_stream(P4, Y4))
     api.thc_decompress(L4, 7, agg7, R.range_M, out, R.ws)
     assert rel_l2(out.cpu().numpy(), o.decompress(P4, 7, Y4, M)) <= 1e-5
+
+
+# ----------------------------------------------------------------------------- the split stage order
+@pytest.mark.parametrize("L,K,n,ef", [(16, 3, 2, False), (17, 2, 2, True), (18, 1, 3, False), (20, 2, 4, True), (21, 1, 1, True),
+                                      (22, 1, 2, False), (23, 1, 1, True), (15, 2, 2, True)])
+def test_split_stage_order(L, K, n, ef):
+    """THC_ORDER_SPLIT: bits 0..9, 13..15, then 10..12, 16..: the first pass works on eight rows of 1024 coordinates.
+    Same checks as for the ascending order, against the oracle running the same order."""
+    block = 1 << L
+    d = block * K
+    P, Lp = both_params(d, block, n, order=1)
+    grads = make_grads(d, n, seed=L * 7 + K)
+    R = GpuRound(Lp, ef=ef)
+    dg = [x.to(DEV) for x in grads]
+    gn = [to_np32(x) for x in grads]
+    efs0 = [np.zeros(d, dtype=F32) for _ in range(n)] if ef else None
+    M_ref = o.prepare_range(P, gn, efs0)
+    R.prepare(2, dg)
+    assert np.all(np.abs(R.range_M.cpu().numpy() - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
+    dM = torch.from_numpy(M_ref).to(DEV)
+    R.compress_all(2, dg, range_M=dM)
+    packed_ref = []
+    for i in range(n):
+        pk, ne = o.compress(P, i, 2, gn[i], None if efs0 is None else efs0[i], M_ref)
+        assert_indices_match(R.packed[i].cpu().numpy(), pk, 4, f"worker {i}")
+        packed_ref.append(pk)
+        if ef:
+            assert rel_l2(R.efs[i].cpu().numpy(), ne) <= 1e-5
+    R.aggregate()
+    Y = o.aggregate(P, packed_ref)
+    assert np.array_equal(R.agg_numpy(), Y)
+    R.decompress(2, range_M=dM)
+    ref = o.decompress(P, 2, Y, M_ref)
+    assert np.array_equal(R.out.cpu().numpy(), ref)

@@ -36,7 +36,7 @@ def test_library_exports_every_declared_symbol():
 def test_params_struct_layout_matches_header():
     # d, block (8+8) n b g agg_bits in_dtype t_p (6*4) seed (8) table (256) = 304 bytes, no padding surprises
     import ctypes
-    assert ctypes.sizeof(api.thc_params) == 304
+    assert ctypes.sizeof(api.thc_params) == 312
     assert api.thc_params.seed.offset == 40 and api.thc_params.table.offset == 48
 
 

@@ -134,6 +134,40 @@ def test_fwht_textbook_size_two_and_involution():
     assert np.array_equal(o.fwht_f32(o.fwht_f32(x)), x * F32(1024))
 
 
+def test_fwht_any_stage_order_is_the_same_transform():
+    # the order of the butterfly stages only moves roundings: every order equals the dense product, and is exact on
+    # small integers
+    rng = np.random.default_rng(1)
+    B = 256
+    H = scipy.linalg.hadamard(B).astype(np.float64)
+    x = rng.standard_normal(B).astype(F32)
+    xi = rng.integers(-20, 20, size=B).astype(F32)
+    for _ in range(5):
+        bits = rng.permutation(8).tolist()
+        got = o.fwht_f32(x, bits).astype(np.float64)
+        assert np.linalg.norm(got - H @ x) <= 1e-6 * np.linalg.norm(H @ x)
+        assert np.array_equal(o.fwht_f32(xi, bits), (H @ xi).astype(F32))
+    assert np.array_equal(o.fwht_f32(x, list(range(8))), o.fwht_f32(x))
+    with pytest.raises(AssertionError):
+        o.fwht_f32(x, [0, 1, 2, 3, 4, 5, 6, 6])                   # every bit exactly once
+
+
+def test_stage_order_conventions():
+    assert o.stage_order(1 << 20, 0) == list(range(20))
+    assert o.stage_order(1 << 20, 1) == list(range(10)) + [13, 14, 15, 10, 11, 12, 16, 17, 18, 19]
+    assert o.stage_order(1 << 16, 1) == list(range(10)) + [13, 14, 15, 10, 11, 12]
+    assert o.stage_order(1 << 15, 1) == list(range(15))           # below 2^16 the split order is the ascending one
+    for L in (10, 13, 16, 22, 25, 27):
+        assert sorted(o.stage_order(1 << L, 1)) == list(range(L))
+    # the two orders differ in roundings only
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(1 << 16).astype(F32)
+    s = o.rademacher_signs(5, 0, 0, 1 << 16)
+    a, b = o.rht_blocks(x, s, 1 << 16, 0), o.rht_blocks(x, s, 1 << 16, 1)
+    assert not np.array_equal(a, b)
+    assert np.linalg.norm(a.astype(np.float64) - b) <= 1e-6 * np.linalg.norm(a)
+
+
 def test_fwht_blocks_along_last_axis():
     rng = np.random.default_rng(3)
     x = rng.standard_normal((5, 256)).astype(F32)
