@@ -64,16 +64,16 @@ struct Plan {
 
 TileMap make_tilemap(int L, int logw, const std::vector<int>& rows, const int (&pref)[3]) {
   TileMap m{};
-  m.L = (uint8_t)L;
-  m.logw = (uint8_t)logw;
-  m.nrows = (uint8_t)rows.size();
-  m.nfixed = (uint8_t)(L - LOG_TILE);
+  m.L = (uint32_t)L;
+  m.logw = (uint32_t)logw;
+  m.nrows = (uint32_t)rows.size();
+  m.nfixed = (uint32_t)(L - LOG_TILE);
   // rows: at most two runs of consecutive bit positions
   size_t run = 0;
   while (run + 1 < rows.size() && rows[run + 1] == rows[run] + 1) ++run;
-  m.n0 = (uint8_t)(rows.empty() ? 0 : run + 1);
-  m.sh0 = (uint8_t)(rows.empty() ? 0 : rows[0]);
-  m.sh1 = (uint8_t)(m.n0 < rows.size() ? rows[m.n0] : 0);
+  m.n0 = (uint32_t)(rows.empty() ? 0 : run + 1);
+  m.sh0 = (uint32_t)(rows.empty() ? 0 : rows[0]);
+  m.sh1 = (uint32_t)(m.n0 < rows.size() ? rows[m.n0] : 0);
   bool taken[32] = {};
   for (int r : rows) taken[r] = true;
   std::vector<int> fixed;
@@ -83,12 +83,16 @@ TileMap make_tilemap(int L, int logw, const std::vector<int>& rows, const int (&
     if (!taken[b]) fixed.push_back(b);
   // cut into runs of consecutive positions (at most four with the orders and splits used here)
   int nrun = 0;
+  uint32_t cum = 0;
   for (size_t i = 0; i < fixed.size();) {
     size_t j = i;
     while (j + 1 < fixed.size() && fixed[j + 1] == fixed[j] + 1) ++j;
     if (nrun == 4) { m.L = 0; return m; }   // cannot happen; L = 0 makes validation fail loudly
-    m.flen[nrun] = (uint8_t)(j - i + 1);
-    m.fpos[nrun] = (uint8_t)fixed[i];
+    const uint32_t len = (uint32_t)(j - i + 1);
+    m.fcum[nrun] = cum;
+    m.fmask[nrun] = (1u << len) - 1u;
+    m.fpos[nrun] = (uint32_t)fixed[i];
+    cum += len;
     ++nrun;
     i = j + 1;
   }

@@ -30,26 +30,25 @@ struct PtrArr {
 // the 8 XCDs) land on the offset bits that measured fastest for that pass.
 // ---------------------------------------------------------------------------------------------
 struct TileMap {
-  uint8_t L;        // log2 of the span the tile index runs over (the block, or 13 for blocks below 8192)
-  uint8_t logw;
-  uint8_t nrows;
-  uint8_t nfixed;   // = L - 13
-  uint8_t n0, sh0, sh1, pad;
-  // the tile index inside the span, cut into up to four runs of consecutive bits: run i is flen[i] bits long
-  // and lands at offset bit fpos[i] (unused runs have length 0)
-  uint8_t flen[4];
-  uint8_t fpos[4];
+  // 32-bit fields throughout: the geometry is uniform per workgroup and stays in scalar registers
+  uint32_t L;        // log2 of the span the tile index runs over (the block, or 13 for blocks below 8192)
+  uint32_t logw;
+  uint32_t nrows;
+  uint32_t nfixed;   // = L - 13
+  uint32_t n0, sh0, sh1;
+  // the tile index inside the span, cut into up to four runs of consecutive bits: run i starts at bit fcum[i]
+  // of the tile index, has mask fmask[i] = 2^length - 1 (0 for an unused run) and lands at offset bit fpos[i]
+  uint32_t fcum[4];
+  uint32_t fmask[4];
+  uint32_t fpos[4];
 };
 
-__device__ __forceinline__ uint64_t tm_base(const TileMap& m, uint64_t tile) {
-  uint64_t off = (tile >> m.nfixed) << m.L;
-  uint32_t tib = (uint32_t)(tile & ((1ull << m.nfixed) - 1));
+__device__ __forceinline__ uint64_t tm_base(const TileMap& m, uint32_t tile) {
+  const uint32_t tib = tile & ((1u << m.nfixed) - 1u);
+  uint32_t off = 0;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    off |= (uint64_t)(tib & ((1u << m.flen[i]) - 1u)) << m.fpos[i];
-    tib >>= m.flen[i];
-  }
-  return off;
+  for (int i = 0; i < 4; ++i) off |= ((tib >> m.fcum[i]) & m.fmask[i]) << m.fpos[i];
+  return ((uint64_t)(tile >> m.nfixed) << m.L) | off;
 }
 
 __device__ __forceinline__ uint32_t tm_row(const TileMap& m, uint32_t r) {
@@ -59,15 +58,19 @@ __device__ __forceinline__ uint32_t tm_row(const TileMap& m, uint32_t r) {
 // ---------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11).  One call yields 128 bits.
 // ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+  return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);   // three-input XOR in one instruction (truth table 0x96)
+}
+
 __device__ __forceinline__ uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                                uint32_t k0, uint32_t k1) {
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
     const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
     const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, k0);
     const uint32_t n1 = (uint32_t)p1;
-    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    const uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, k1);
     const uint32_t n3 = (uint32_t)p0;
     c0 = n0; c1 = n1; c2 = n2; c3 = n3;
     k0 += 0x9E3779B9u;

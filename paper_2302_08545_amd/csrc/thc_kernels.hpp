@@ -187,7 +187,7 @@ struct HiGeom {
   static constexpr int W = 1 << LOGW;
   const TileMap& m;
   uint64_t base;   // coordinate of (row 0, col 0)
-  __device__ HiGeom(uint64_t tile, const TileMap& m_) : m(m_), base(tm_base(m_, tile)) {}
+  __device__ HiGeom(uint32_t tile, const TileMap& m_) : m(m_), base(tm_base(m_, tile)) {}
   // offset of a tile index from `base`: 32 bits are enough (blocks are at most 2^27 coordinates), so device
   // addresses can be formed as uniform 64-bit base + 32-bit per-lane offset
   __device__ uint32_t off(int idx) const { return tm_row(m, (uint32_t)idx >> LOGW) + (uint32_t)(idx & (W - 1)); }
@@ -363,7 +363,7 @@ struct QuantScalars {
 
 template <bool CFOLD>
 __device__ __forceinline__ void quantize8(const float (&hv)[8], const uint4 rnd, const QuantScalars s,
-                                          const uint2* lut, uint32_t (&z)[8]) {
+                                          const uint4* lut, uint32_t (&z)[8]) {
   const uint32_t rw[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -371,12 +371,11 @@ __device__ __forceinline__ void quantize8(const float (&hv)[8], const uint4 rnd,
     const float xc = __builtin_amdgcn_fmed3f(v, s.lo, s.M);
     const float y16 = (xc - s.lo) * s.sc16;
     const uint32_t ki = (uint32_t)y16;
-    const uint2 ent = lut[(ki >> 16) & 255u];
+    const uint4 ent = lut[(ki >> 16) & 255u];
     const float t16 = y16 - __uint_as_float(ent.x);
-    const float wd = (float)(ent.y & 255u);
     const float hf = (float)((e & 1) ? (rw[e >> 1] >> 16) : (rw[e >> 1] & 0xFFFFu));
-    const float prod = __builtin_fmaf(hf, wd, 0.5f * wd);
-    z[e] = (ent.y >> 8) + (prod < t16 ? 1u : 0u);
+    const float prod = __builtin_fmaf(hf, __uint_as_float(ent.y), __uint_as_float(ent.z));
+    z[e] = ent.w + (prod < t16 ? 1u : 0u);
   }
 }
 
@@ -405,11 +404,15 @@ __device__ __forceinline__ void store_packed8(uint8_t* packed, uint64_t j, uint3
   }
 }
 
-__device__ __forceinline__ void build_quant_lut(const QuantArgs& a, uint2* lut, int t) {
-  if (t < 256) {
-    const uint32_t ent = a.lut[t];
-    lut[t] = make_uint2(__float_as_uint((float)(ent & 255u) * 65536.0f), ent >> 8);
-  }
+// LDS entry of grid cell k: {lo * 2^16, wd, wd / 2 (all binary32, exact), z0}
+__device__ __forceinline__ uint4 quant_lut_entry(uint32_t ent) {
+  const float wd = (float)((ent >> 8) & 255u);
+  return make_uint4(__float_as_uint((float)(ent & 255u) * 65536.0f), __float_as_uint(wd), __float_as_uint(0.5f * wd),
+                    ent >> 16);
+}
+
+__device__ __forceinline__ void build_quant_lut(const QuantArgs& a, uint4* lut, int t) {
+  if (t < 256) lut[t] = quant_lut_entry(a.lut[t]);
 }
 
 // g / (M - m) * 2^16: the width in binary64, the quotient rounded once to binary32 (0 for an empty range)
@@ -425,7 +428,7 @@ __device__ __forceinline__ float lower_of(const float* range_m, uint64_t blk, fl
 template <int R, bool CFOLD>
 __global__ __launch_bounds__(NT, 8) void k_fwd_hi_quant(const QuantArgs a) {
   __shared__ __align__(16) float lds[TILE];
-  __shared__ uint2 lut[256];
+  __shared__ uint4 lut[256];
   __shared__ float sM[8], sLo[8], sScale[8];
 
   const int t = threadIdx.x;
@@ -888,13 +891,12 @@ struct UQuantArgs {
 
 template <bool BF16>
 __global__ __launch_bounds__(NT) void k_uniform_quant(const UQuantArgs a) {
-  __shared__ uint2 lut[256];
+  __shared__ uint4 lut[256];
   __shared__ float sM[8], sLo[8], sScale[8], sStep[8];
   const int t = threadIdx.x;
   const uint64_t off = (uint64_t)blockIdx.x << LOG_TILE;
   if (t < 256) {
-    const uint32_t ent = a.lut[t];
-    lut[t] = make_uint2(__float_as_uint((float)(ent & 255u) * 65536.0f), ent >> 8);
+    lut[t] = quant_lut_entry(a.lut[t]);
   }
   const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
   if (t < nblk) {
