@@ -110,19 +110,17 @@ Plan make_plan(uint64_t block, uint32_t stage_order) {
   pl.L = ilog2(block);
   pl.L1 = pl.L < LOG_TILE ? pl.L : LOG_TILE;
   pl.split = stage_order == THC_ORDER_SPLIT && pl.L >= 16;
-  int rem = pl.L - pl.L1;
-  pl.nmid = 0;
-  if (pl.split && rem > 7) {
-    // a tile's columns are its low offset bits, so a pass that owns bit 10 must own 10, 11 and 12 (1024-wide rows)
-    pl.mid[pl.nmid++] = 3;
-    rem -= 3;
-  }
-  pl.R = rem < 7 ? rem : 7;
-  rem -= pl.R;
-  while (rem > 0) {
-    const int m = rem < 7 ? rem : 7;
-    pl.mid[pl.nmid++] = m;
-    rem -= m;
+  // The bits left after the lo pass go to ceil(rem / 7) strided passes of nearly equal size (wider rows make
+  // longer contiguous segments); the last one, fused with the quantizer or the final scaling, gets the smallest.
+  // In the split order the first of them starts with bits 10, 11, 12: its rows are 1024 coordinates wide at most,
+  // so it must own all three, which any share of at least 3 bits guarantees.
+  const int rem = pl.L - pl.L1;
+  const int npass = rem > 0 ? (rem + 6) / 7 : 1;
+  pl.nmid = npass - 1;
+  pl.R = rem / npass;
+  for (int m = 0, left = rem - pl.R; m < pl.nmid; ++m) {
+    pl.mid[m] = (left + (pl.nmid - m) - 1) / (pl.nmid - m);
+    left -= pl.mid[m];
   }
   const int Lg = pl.L < LOG_TILE ? LOG_TILE : pl.L;   // blocks below 8192: tiles are just 8192 consecutive coordinates
   // bits still to do after the lo pass, in processing order
@@ -317,7 +315,7 @@ int thc_prepare_range(const thc_params* p, uint64_t round, const void* const* gr
   launch_fwd_lo(pl, a, p->in_dtype == THC_DTYPE_BF16, ef != nullptr, tiles_of(p->d), p->n, s);
   if (range_M) {
     RangeArgs r{a.partials, range_M, p->d, p->n, (uint32_t)pl.L, (uint32_t)pl.L1, p->t_p};
-    k_range<<<dim3((unsigned)(p->d / p->block)), dim3(64), 0, s>>>(r);
+    k_range<<<dim3((unsigned)(p->d / p->block)), dim3(RANGE_NT), 0, s>>>(r);
   }
   return check_launch();
 }

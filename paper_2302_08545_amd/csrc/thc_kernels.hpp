@@ -159,20 +159,31 @@ struct RangeArgs {
   float t_p;
 };
 
-__global__ __launch_bounds__(64) void k_range(const RangeArgs a) {
+constexpr int RANGE_NT = 1024;
+
+// One workgroup per block: Sigma x^2 of every worker in a fixed summation order (thread-strided partial sums,
+// wave butterflies, then the 16 wave totals in sequence), the maximum over workers, and M.
+__global__ __launch_bounds__(RANGE_NT) void k_range(const RangeArgs a) {
+  __shared__ double wsum[MAXW][RANGE_NT / 64];
   const uint64_t k = blockIdx.x;
-  const int lane = threadIdx.x;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const uint32_t ppb = 1u << (a.L - a.L1);           // partials per block
   const uint64_t per_worker = a.d >> a.L1;
-  double smax = 0.0;
   for (uint32_t i = 0; i < a.n; ++i) {
     const double* p = a.partials + (uint64_t)i * per_worker + k * ppb;
     double s = 0.0;
-    for (uint32_t j = lane; j < ppb; j += 64) s += p[j];
+    for (uint32_t j = t; j < ppb; j += RANGE_NT) s += p[j];
     s = wave_sum(s);
-    smax = s > smax ? s : smax;
+    if (lane == 0) wsum[i][wave] = s;
   }
-  if (lane == 0) {
+  __syncthreads();
+  if (t == 0) {
+    double smax = 0.0;
+    for (uint32_t i = 0; i < a.n; ++i) {
+      double s = 0.0;
+      for (int w = 0; w < RANGE_NT / 64; ++w) s += wsum[i][w];
+      smax = s > smax ? s : smax;
+    }
     const double M = ((double)a.t_p * __builtin_sqrt(smax)) / __builtin_sqrt((double)(1ull << a.L));
     a.range_M[k] = (float)M;
   }
