@@ -389,6 +389,23 @@ int thc_aggregate(const thc_params* p, const uint8_t* const* packed, void* agg_o
     a.n = p->n;
     std::memcpy(a.tb, p->table, 16);
     k_aggregate_b4w8<<<dim3((unsigned)((a.nvec + 255) / 256)), dim3(256), 0, s>>>(a);
+  } else if (p->b == 2 && p->agg_bits == 8) {
+    AggB2Args a{};
+    for (uint32_t i = 0; i < p->n; ++i) a.packed.p[i] = packed[i];
+    a.out = static_cast<uint8_t*>(agg_out);
+    a.nvec = p->d / 64;
+    a.n = p->n;
+    std::memcpy(&a.tb, p->table, 4);
+    k_aggregate_b2w8<<<dim3((unsigned)((a.nvec + 255) / 256)), dim3(256), 0, s>>>(a);
+  } else if (p->b == 4 && p->agg_bits == 16) {
+    AggB4W16Args a{};
+    for (uint32_t i = 0; i < p->n; ++i) a.packed.p[i] = packed[i];
+    a.out = static_cast<uint8_t*>(agg_out);
+    a.nvec = p->d / 32;
+    a.n = p->n;
+    a.chunk = 255u / p->g;              // g <= 255, so at least one worker per run
+    std::memcpy(a.tb, p->table, 16);
+    k_aggregate_b4w16<<<dim3((unsigned)((a.nvec + 255) / 256)), dim3(256), 0, s>>>(a);
   } else {
     AggArgs a{};
     for (uint32_t i = 0; i < p->n; ++i) a.packed.p[i] = packed[i];

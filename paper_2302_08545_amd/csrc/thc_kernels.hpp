@@ -1101,4 +1101,85 @@ __global__ __launch_bounds__(256) void k_aggregate_b4w8(const AggB4Args a) {
   dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
 }
 
+// 4-bit indices -> 16-bit sums (g*n above 255).  Same lookups; workers are taken in runs of `chunk` =
+// floor(255 / g), inside which the byte-wise sums cannot carry, and every run is then widened into 16-bit lanes.
+struct AggB4W16Args {
+  PtrArr packed;
+  uint8_t* out;
+  uint64_t nvec;    // d / 32
+  uint32_t n, chunk;
+  uint32_t tb[4];
+};
+
+__global__ __launch_bounds__(256) void k_aggregate_b4w16(const AggB4W16Args a) {
+  const uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (v >= a.nvec) return;
+  const uint32_t tb[4] = {a.tb[0], a.tb[1], a.tb[2], a.tb[3]};
+  uint32_t acc[16];   // acc[4k + m] = sums of coordinates 8k + 2m (low half) and 8k + 2m + 1 (high half)
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0;
+  for (uint32_t i0 = 0; i0 < a.n; i0 += a.chunk) {
+    const uint32_t i1 = (i0 + a.chunk < a.n) ? i0 + a.chunk : a.n;
+    uint32_t ev[4] = {0, 0, 0, 0}, od[4] = {0, 0, 0, 0};
+    for (uint32_t i = i0; i < i1; ++i) {
+      const uint4 r = reinterpret_cast<const uint4*>(a.packed.p[i])[v];
+      const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        ev[k] += lut16x4(w[k] & 0x0F0F0F0Fu, tb);
+        od[k] += lut16x4((w[k] >> 4) & 0x0F0F0F0Fu, tb);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      acc[4 * k + 0] += __builtin_amdgcn_perm(od[k], ev[k], 0x0C040C00u);
+      acc[4 * k + 1] += __builtin_amdgcn_perm(od[k], ev[k], 0x0C050C01u);
+      acc[4 * k + 2] += __builtin_amdgcn_perm(od[k], ev[k], 0x0C060C02u);
+      acc[4 * k + 3] += __builtin_amdgcn_perm(od[k], ev[k], 0x0C070C03u);
+    }
+  }
+  uint4* dst = reinterpret_cast<uint4*>(a.out + v * 64);
+#pragma unroll
+  for (int k = 0; k < 4; ++k) dst[k] = make_uint4(acc[4 * k], acc[4 * k + 1], acc[4 * k + 2], acc[4 * k + 3]);
+}
+
+// 2-bit indices -> 8-bit sums.  One thread owns 64 coordinates (16 bytes of every stream); the four table
+// values sit in one register; field f of every byte is looked up with one byte permute, so acc[k][f] holds the
+// sums of coordinates 16k + 4*byte + f, and a 4x4 byte transpose restores coordinate order at the end.
+struct AggB2Args {
+  PtrArr packed;
+  uint8_t* out;
+  uint64_t nvec;    // d / 64
+  uint32_t n;
+  uint32_t tb;      // table bytes 0..3, little endian
+};
+
+__global__ __launch_bounds__(256) void k_aggregate_b2w8(const AggB2Args a) {
+  const uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (v >= a.nvec) return;
+  uint32_t acc[4][4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int f = 0; f < 4; ++f) acc[k][f] = 0;
+  for (uint32_t i = 0; i < a.n; ++i) {
+    const uint4 r = reinterpret_cast<const uint4*>(a.packed.p[i])[v];
+    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int f = 0; f < 4; ++f) acc[k][f] += __builtin_amdgcn_perm(0u, a.tb, (w[k] >> (2 * f)) & 0x03030303u);
+  }
+  uint4* dst = reinterpret_cast<uint4*>(a.out + v * 64);
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const uint32_t p0 = __builtin_amdgcn_perm(acc[k][1], acc[k][0], 0x05010400u);   // bytes 0, 1 of fields 0, 1
+    const uint32_t p1 = __builtin_amdgcn_perm(acc[k][1], acc[k][0], 0x07030602u);   // bytes 2, 3
+    const uint32_t q0 = __builtin_amdgcn_perm(acc[k][3], acc[k][2], 0x05010400u);
+    const uint32_t q1 = __builtin_amdgcn_perm(acc[k][3], acc[k][2], 0x07030602u);
+    dst[k] = make_uint4(__builtin_amdgcn_perm(q0, p0, 0x05040100u), __builtin_amdgcn_perm(q0, p0, 0x07060302u),
+                        __builtin_amdgcn_perm(q1, p1, 0x05040100u), __builtin_amdgcn_perm(q1, p1, 0x07060302u));
+  }
+}
+
 }  // namespace thc

@@ -137,7 +137,9 @@ def test_prepare_range_and_compress(block, K, n):
 @pytest.mark.parametrize("b,g,agg_bits,n", [(4, 30, 8, 8), (4, 30, 8, 1), (4, 30, 8, 3), (4, 30, 16, 16), (2, 8, 8, 16),
                                             (4, 15, 8, 17), (1, 1, 8, 64), (8, 255, 16, 5), (2, 3, 16, 64), (4, 36, 16, 64),
                                             (3, 12, 8, 10), (3, 7, 6, 9), (4, 30, 7, 4), (4, 30, 9, 16), (5, 40, 11, 33),
-                                            (2, 8, 7, 15), (6, 63, 13, 64), (7, 200, 16, 9), (1, 1, 1, 1), (4, 30, 5, 1)])
+                                            (2, 8, 7, 15), (6, 63, 13, 64), (7, 200, 16, 9), (1, 1, 1, 1), (4, 30, 5, 1),
+                                            (4, 255, 16, 7), (4, 100, 16, 64), (4, 128, 16, 3), (4, 85, 16, 10),
+                                            (2, 8, 8, 1), (2, 3, 8, 64), (2, 8, 8, 31), (2, 255, 8, 1)])
 def test_aggregate_bit_exact(b, g, agg_bits, n):
     d = 5 * 1024
     T = table_for(b, g) if g > 2 ** b - 1 else list(range(2 ** b))
@@ -281,6 +283,64 @@ def test_blocks_that_need_a_middle_pass(L):
     R.decompress(0, range_M=torch.from_numpy(M_ref).to(DEV))
     ref = o.decompress(P, 0, o.aggregate(P, [pk]), M_ref)
     assert rel_l2(R.out.cpu().numpy(), ref) <= 1e-5
+
+
+@pytest.mark.parametrize("order", [1, 0], ids=["split-order", "ascending-order"])
+def test_largest_block_against_closed_forms(order):
+    """B = 2^27, the largest block the library takes (13 + 7 + 7 bits).  The oracle needs minutes there, so the
+    inputs are chosen to make every butterfly exact in any order: two nonzero coordinates going in
+    (RHT(x)[j] = c (s1 h(j,k1) + 2 s2 h(j,k2)), h(j,k) = (-1)^popcount(j & k)), and sums that follow one Hadamard
+    column coming back (the inverse is nonzero at coordinates 0 and k1 only).  The quantizer is the oracle's, on
+    sampled tiles."""
+    Lg = 27
+    B = 1 << Lg
+    k1, k2 = 0x2B5A6C9, 0x5D3C0F2
+    P, Lp = both_params(B, B, 1, order=order)
+    R = GpuRound(Lp)
+    x = torch.zeros(B, dtype=torch.float32, device=DEV)
+    x[k1], x[k2] = 1.0, 2.0
+    R.prepare(3, [x])
+    xn = np.zeros(B, dtype=F32)
+    xn[k1], xn[k2] = 1.0, 2.0
+    M_ref = o.prepare_range(P, [xn])
+    assert abs(float(R.range_M.cpu()[0]) - float(M_ref[0])) <= 2.0 ** -23 * float(M_ref[0])
+    R.compress_all(3, [x], range_M=torch.from_numpy(M_ref).to(DEV))
+    packed = R.packed[0].cpu().numpy()
+    s1 = float(o.rademacher_signs(P.seed, 3, k1, 1)[0])
+    s2 = float(o.rademacher_signs(P.seed, 3, k2, 1)[0])
+    c = o.rht_scale(B)
+
+    def h(j, k):
+        v = j & k
+        for sh in (16, 8, 4, 2, 1):
+            v = v ^ (v >> sh)
+        return 1 - 2 * (v & 1)
+
+    T = 8192
+    Pt = o.Params(d=T, block=T, n=1, b=P.b, g=P.g, t_p=P.t_p, seed=P.seed, table=P.table, agg_bits=8, order=order)
+    rng = np.random.default_rng(27)
+    tiles = [0, B // T - 1] + [int(t) for t in rng.integers(0, B // T, size=30)]
+    for t in tiles:
+        j = np.arange(t * T, (t + 1) * T, dtype=np.int64)
+        Rt = ((s1 * h(j, k1) + 2.0 * s2 * h(j, k2)).astype(F32) * c).astype(F32)
+        z = o.quantize_rotated(Pt, Rt, M_ref, o.sq_halfwords(P.seed, 3, 0, t * T, T))
+        assert np.array_equal(packed[t * T // 2:(t + 1) * T // 2], o.pack_indices(z, P.b)), f"tile {t}"
+
+    # decompression: Y = 20 where h(j, k1) = +1 and 10 where it is -1
+    j = torch.arange(B, dtype=torch.int64, device=DEV)
+    R.agg.copy_((15 + 5 * h(j, k1)).to(torch.uint8))
+    del j
+    R.decompress(3, range_M=torch.from_numpy(M_ref).to(DEV))
+    _, _, step_n = o.block_scalars(P, M_ref)
+    a = F32(F32(F32(20.0) * step_n[0]) - M_ref[0])
+    b = F32(F32(F32(10.0) * step_n[0]) - M_ref[0])
+    half = F32(2.0 ** (Lg - 1))
+    sg0 = o.rademacher_signs(P.seed, 3, 0, 1)[0]
+    want0 = F32(F32(F32(a + b) * half) * c) * sg0
+    want1 = F32(F32(F32(a - b) * half) * c) * F32(s1)
+    out = R.out
+    assert float(out[0].cpu()) == float(want0) and float(out[k1].cpu()) == float(want1)
+    assert int(torch.count_nonzero(out).cpu()) == 2
 
 
 # ----------------------------------------------------------------------------- degenerate cases
