@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -249,17 +250,35 @@ void run_mids(const Plan& pl, float* x, uint64_t d, hipStream_t s) {
   }
 }
 
-// inverse transform of one vector that k_inv_lo is about to produce in `wsx`
-int run_inverse(const thc_params* p, const Plan& pl, InvLoArgs lo, float* wsx, InvHiArgs hi, hipStream_t s) {
+// inverse transform of `len` coordinates that k_inv_lo is about to produce in `wsx`
+void run_inverse(const thc_params* p, const Plan& pl, InvLoArgs lo, float* wsx, InvHiArgs hi, uint64_t len,
+                 hipStream_t s) {
   lo.tm = pl.lo;
-  launch_inv_lo(pl, lo, tiles_of(p->d), s);
-  run_mids(pl, wsx, p->d, s);
+  lo.ws_x = wsx;
+  lo.d = len;
+  launch_inv_lo(pl, lo, tiles_of(len), s);
+  run_mids(pl, wsx, len, s);
   hi.x = wsx;
-  hi.d = p->d;
+  hi.d = len;
   hi.tm = pl.hi;
   hi.c = (float)(1.0 / std::sqrt((double)p->block));
-  dispatch_0_7<LaunchInvHi>(pl.R, hi, tiles_of(p->d), s);
-  return check_launch();
+  dispatch_0_7<LaunchInvHi>(pl.R, hi, tiles_of(len), s);
+}
+
+// Kernels that hand a vector to each other through the workspace (inverse lo -> hi, middle passes, the error-feedback
+// chain) work on pieces of this many coordinates, one after the other, and the intermediate of every piece after the
+// first lands on the same 128 MB of the workspace: it then stays in the 256 MB memory-side cache between its
+// writer and its reader instead of travelling to HBM and back.  Whole blocks; random streams are indexed by
+// global coordinate (the kernels' j0).
+// The environment variable THC_PIECE_LOG2 (10..40) overrides the default piece of 2^25 coordinates: results do not
+// depend on it, only the speed (and tests use it to cut small vectors into several pieces).
+uint64_t piece_coords(const thc_params* p) {
+  uint64_t target = 1ull << 25;
+  if (const char* e = std::getenv("THC_PIECE_LOG2")) {
+    const long v = std::strtol(e, nullptr, 10);
+    if (v >= 10 && v <= 40) target = 1ull << v;
+  }
+  return p->block > target ? p->block : target;
 }
 
 const char* const kNames[] = {"THC_OK", "THC_EINVAL", "THC_ETABLE", "THC_EOVERFLOW", "THC_EUNSUPPORTED", "THC_ELAUNCH"};
@@ -331,13 +350,7 @@ int thc_compress(const thc_params* p, uint32_t worker_id, uint64_t round, const 
   hipStream_t s = static_cast<hipStream_t>(stream);
   float* wsx = static_cast<float*>(ws) + (size_t)worker_id * p->d;
 
-  run_mids(pl, wsx, p->d, s);
-
   QuantArgs q{};
-  q.x = wsx;
-  q.range_M = range_M;
-  q.packed = packed_out;
-  q.d = p->d;
   q.tm = pl.hi;
   q.L = (uint32_t)pl.L;
   q.b = p->b;
@@ -348,28 +361,44 @@ int thc_compress(const thc_params* p, uint32_t worker_id, uint64_t round, const 
   q.k1 = (uint32_t)(p->seed >> 32);
   q.c = (float)(1.0 / std::sqrt((double)p->block));
   fill_lut(p, q.lut);   // per grid cell k: the largest index z0 with T[z0] <= k, its value and the gap to the next
-  dispatch_0_7<LaunchQuant>(pl.R, q, (pl.L & 1) == 0, tiles_of(p->d), s);
-
+  InvLoArgs lo{};
+  InvHiArgs hi{};
   if (ef_inout) {
-    InvLoArgs lo{};
-    lo.src = packed_out;
-    lo.range_M = range_M;
-    lo.ws_x = wsx;
-    lo.d = p->d;
     lo.L = (uint32_t)pl.L;
     lo.src_bits = p->b;
     lo.use_table = 1;
     lo.divisor = p->g;
     std::memcpy(lo.table, p->table, 256);
-    InvHiArgs hi{};
-    hi.out = ef_inout;
-    hi.grad = grad;
     hi.round = (uint32_t)round;
     hi.k0 = q.k0;
     hi.k1 = q.k1;
     hi.mode = 1;
     hi.bf16 = p->in_dtype == THC_DTYPE_BF16;
-    return run_inverse(p, pl, lo, wsx, hi, s);
+  }
+  // Pieces pay off (measured) once three or more kernels follow each other on the same data, as in the
+  // error-feedback chain; every extra launch costs about 7 us, which a chain of two does not earn back.
+  const uint64_t piece = ef_inout ? piece_coords(p) : p->d;
+  const size_t in_size = p->in_dtype == THC_DTYPE_BF16 ? 2 : 4;
+  for (uint64_t j0 = 0; j0 < p->d; j0 += piece) {
+    const uint64_t len = p->d - j0 < piece ? p->d - j0 : piece;
+    const float* rM = range_M + j0 / p->block;
+    uint8_t* pk = packed_out + j0 / 8 * p->b;
+    run_mids(pl, wsx + j0, len, s);
+    q.x = wsx + j0;
+    q.range_M = rM;
+    q.packed = pk;
+    q.d = len;
+    q.j0 = j0;
+    dispatch_0_7<LaunchQuant>(pl.R, q, (pl.L & 1) == 0, tiles_of(len), s);
+    if (ef_inout) {
+      lo.src = pk;
+      lo.range_M = rM;
+      hi.out = ef_inout + j0;
+      hi.grad = static_cast<const char*>(grad) + j0 * in_size;
+      hi.j0 = j0;
+      // the first piece's own part of the workspace is free once its quantizer has run, and serves all later pieces
+      run_inverse(p, pl, lo, wsx, hi, len, s);
+    }
   }
   return check_launch();
 }
@@ -431,21 +460,25 @@ int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const f
   hipStream_t s = static_cast<hipStream_t>(stream);
   float* wsx = static_cast<float*>(ws);
   InvLoArgs lo{};
-  lo.src = agg;
-  lo.range_M = range_M;
-  lo.ws_x = wsx;
-  lo.d = p->d;
   lo.L = (uint32_t)pl.L;
   lo.src_bits = p->agg_bits;
   lo.use_table = 0;
   lo.divisor = p->g * p->n;
   InvHiArgs hi{};
-  hi.out = out;
   hi.round = (uint32_t)round;
   hi.k0 = (uint32_t)p->seed;
   hi.k1 = (uint32_t)(p->seed >> 32);
   hi.mode = 0;
-  return run_inverse(p, pl, lo, wsx, hi, s);
+  const uint64_t piece = pl.nmid > 0 ? piece_coords(p) : p->d;   // lo -> hi alone does not earn the launches back
+  for (uint64_t j0 = 0; j0 < p->d; j0 += piece) {
+    const uint64_t len = p->d - j0 < piece ? p->d - j0 : piece;
+    lo.src = static_cast<const uint8_t*>(agg) + j0 / 8 * p->agg_bits;
+    lo.range_M = range_M + j0 / p->block;
+    hi.out = out + j0;
+    hi.j0 = j0;
+    run_inverse(p, pl, lo, wsx, hi, len, s);
+  }
+  return check_launch();
 }
 
 // ---- uniform THC (Alg. 1) -----------------------------------------------------------------------
@@ -563,7 +596,7 @@ int thc_uniform_compress(const thc_params* p, uint32_t worker_id, uint64_t round
     hi.k1 = q.k1;
     hi.mode = 1;
     hi.bf16 = p->in_dtype == THC_DTYPE_BF16;
-    return run_inverse(p, pl, lo, wsx, hi, s);
+    run_inverse(p, pl, lo, wsx, hi, p->d, s);
   }
   return check_launch();
 }
@@ -599,7 +632,8 @@ int thc_uniform_decompress(const thc_params* p, uint64_t round, const void* agg,
   hi.k0 = (uint32_t)p->seed;
   hi.k1 = (uint32_t)(p->seed >> 32);
   hi.mode = 0;
-  return run_inverse(p, pl, lo, wsx, hi, s);
+  run_inverse(p, pl, lo, wsx, hi, p->d, s);
+  return check_launch();
 }
 
 double thc_threshold(double p) {

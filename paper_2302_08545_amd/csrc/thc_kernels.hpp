@@ -360,6 +360,7 @@ struct QuantArgs {
   const float* range_m;    // K floats, or null: m = -M
   uint8_t* packed;         // d*b/8 bytes
   uint64_t d;
+  uint64_t j0;             // global coordinate of x[0] (a multiple of B): the random streams are indexed globally
   TileMap tm;
   uint32_t L;              // log2 B
   uint32_t b, g;
@@ -463,7 +464,7 @@ __global__ __launch_bounds__(NT, 8) void k_fwd_hi_quant(const QuantArgs a) {
     float v[2][8];
     hi_back<R>(lds, t, idx, v);
     const QuantScalars s{sM[0], sLo[0], sScale[0], a.c};
-    const uint64_t q0 = g.base >> 3;            // tiles start on multiples of 64 coordinates
+    const uint64_t q0 = (a.j0 + g.base) >> 3;   // tiles start on multiples of 64 coordinates
     uint8_t* const pk0 = a.packed + (g.base >> 3) * a.b;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -500,7 +501,7 @@ __global__ __launch_bounds__(NT, 8) void k_fwd_hi_quant(const QuantArgs a) {
       const float4 p0 = *reinterpret_cast<const float4*>(&lds[idx]);
       const float4 p1 = *reinterpret_cast<const float4*>(&lds[idx + 4]);
       const float hv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-      const uint64_t q = j >> 3;
+      const uint64_t q = (a.j0 + j) >> 3;
       const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, a.worker, a.k0, a.k1);
       uint32_t z[8];
       quantize8<false>(hv, rnd, s, lut, z);
@@ -641,6 +642,7 @@ struct InvHiArgs {
   float* out;          // d floats
   const void* grad;    // mode 1 only
   uint64_t d;
+  uint64_t j0;         // global coordinate of x[0] (a multiple of B), for the diagonal's random stream
   TileMap tm;
   uint32_t round, k0, k1;
   uint32_t mode, bf16;
@@ -672,7 +674,7 @@ __global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
   if constexpr (R >= 2) {
     hi_front<R>(a.x, g, lds, t);
     // 32 consecutive tile indices are 32 consecutive coordinates (rows are at least 64 wide)
-    if (t < TILE / 32) sgn[t] = sign_word(g.coord(32 * t), a.round, a.k0, a.k1);
+    if (t < TILE / 32) sgn[t] = sign_word(a.j0 + g.coord(32 * t), a.round, a.k0, a.k1);
     int idx[2];
     float v[2][8];
     hi_back<R>(lds, t, idx, v);
@@ -687,7 +689,7 @@ __global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
       *reinterpret_cast<float4*>(a.out + j + 4) = o1;
     }
   } else {
-    if (t < TILE / 32) sgn[t] = sign_word(g.coord(32 * t), a.round, a.k0, a.k1);
+    if (t < TILE / 32) sgn[t] = sign_word(a.j0 + g.coord(32 * t), a.round, a.k0, a.k1);
     hi_load_to_lds<R>(a.x, g, a.d, lds, t);
     lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, int, float) {});
     __syncthreads();

@@ -243,6 +243,40 @@ def test_error_feedback_rounds():
             R.efs[i].copy_(torch.from_numpy(efs_ref[i]))
 
 
+@pytest.mark.parametrize("L,K,n,bf16,order", [(12, 11, 2, False, 0), (16, 5, 2, True, 1), (18, 3, 1, False, 1),
+                                                 (21, 2, 1, False, 1)])
+def test_piecewise_processing_matches_the_oracle(L, K, n, bf16, order, monkeypatch):
+    """thc_compress (error-feedback chain) and thc_decompress cut long vectors into pieces that share one part of
+    the workspace.  With the piece forced down to 2^14 coordinates (or one block, if larger) these vectors take
+    several pieces, the last one shorter; packed bytes, error feedback and the output must not change."""
+    monkeypatch.setenv("THC_PIECE_LOG2", "14")
+    block = 1 << L
+    d = block * K
+    P, Lp = both_params(d, block, n, bf16=bf16, order=order)
+    R = GpuRound(Lp, ef=True)
+    efs_ref = [np.zeros(d, dtype=F32) for _ in range(n)]
+    for rnd in range(2):
+        grads = make_grads(d, n, seed=70 + rnd, bf16=bf16)
+        dg = [x.to(DEV) for x in grads]
+        gn = [to_np32(x) for x in grads]
+        M_ref = o.prepare_range(P, gn, efs_ref)
+        R.prepare(rnd, dg)
+        R.compress_all(rnd, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+        pks = []
+        for i in range(n):
+            pk, ne = o.compress(P, i, rnd, gn[i], efs_ref[i], M_ref)
+            assert_indices_match(R.packed[i].cpu().numpy(), pk, 4, f"round {rnd} worker {i}")
+            assert rel_l2(R.efs[i].cpu().numpy(), ne) <= 1e-5, f"round {rnd} worker {i}"
+            efs_ref[i] = ne
+            R.efs[i].copy_(torch.from_numpy(ne))
+            R.packed[i].copy_(torch.from_numpy(pk))
+            pks.append(pk)
+        R.aggregate()
+        R.decompress(rnd, range_M=torch.from_numpy(M_ref).to(DEV))
+        ref = o.decompress(P, rnd, o.aggregate(P, pks), M_ref)
+        assert rel_l2(R.out.cpu().numpy(), ref) <= 1e-5
+
+
 def test_bf16_gradients_with_error_feedback():
     block, K, n = 1 << 13, 2, 2
     d = block * K
