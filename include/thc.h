@@ -33,6 +33,9 @@
  *     (j mod 32) of word ((j div 32) mod 4) of Philox(counter (q, q>>32, round, 0x80000000)), q = j div 128.
  *     Rounding draw of worker i: coordinate j takes 16-bit half (j mod 8) (low half first) of
  *     Philox(counter (q, q>>32, round, i)), q = j div 8; u = (half + 1/2) / 2^16.
+ *     j is the coordinate's position in the whole vector: a call whose buffers hold only blocks
+ *     [first_block, first_block + d/block) of a longer vector (a shard, a piece) sets thc_params.first_block
+ *     and computes exactly what the call on the whole vector computes for those blocks.
  *   - Butterflies of the Hadamard transform run in the stage order of thc_params.stage_order, in binary32,
  *     without fused multiply-add; packed bytes and aggregated sums are therefore reproducible bit for bit.
  */
@@ -79,7 +82,7 @@ typedef struct thc_params {
   uint64_t seed;       /* shared by all workers and the decompressor                                       */
   uint8_t  table[256]; /* T[0 .. 2^b-1]; see thc_solve_table                                               */
   uint32_t stage_order;/* THC_ORDER_ASCENDING or THC_ORDER_SPLIT                                           */
-  uint32_t reserved;   /* must be 0                                                                        */
+  uint32_t first_block;/* index, in the whole vector, of the first block these buffers hold (0 for a whole vector) */
 } thc_params;
 
 /* Library version (major*10000 + minor*100 + patch). */
@@ -90,7 +93,10 @@ const char* thc_strerror(int status);
 
 /* Bytes of device workspace the four calls below need for these parameters (host call, no GPU work).
  * The workspace holds the half-rotated vectors of all n workers between thc_prepare_range and
- * thc_compress (n*d binary32 values) plus the partial sums of squares. */
+ * thc_compress (n*d binary32 values) plus the partial sums of squares; thc_compress with error feedback and
+ * thc_decompress use it as scratch, so its contents are unspecified after them.  Long vectors go through those
+ * two in pieces of 2^25 coordinates that share one part of the workspace (it stays in the memory-side cache);
+ * the environment variable THC_PIECE_LOG2 changes the piece size, never the results. */
 int thc_workspace_bytes(const thc_params* p, size_t* bytes_out /* host */);
 
 /* Preliminary stage (Alg. 3: x_i = grad_i + e_i; send ||x_i||, receive the maximum -- in parallel with

@@ -430,50 +430,52 @@ def decompress(P: Params, rnd: int, Y: np.ndarray, range_M: np.ndarray, j0: int 
 # Uniform THC (Alg. 1): identity table with g = 2^b - 1, range = global minimum and maximum of what is
 # quantized (the gradients themselves, or their RHT when rotation is switched on -- the ablation of App. C).
 # --------------------------------------------------------------------------- #
-def uniform_values(P: Params, rnd: int, grad: np.ndarray, ef: Optional[np.ndarray], rotate: bool) -> np.ndarray:
-    """What a worker quantizes: x = grad + e, rotated block-wise when `rotate`."""
+def uniform_values(P: Params, rnd: int, grad: np.ndarray, ef: Optional[np.ndarray], rotate: bool,
+                   j0: int = 0) -> np.ndarray:
+    """What a worker quantizes: x = grad + e, rotated block-wise when `rotate`.  j0 is the global index of the
+    first coordinate (as in `compress`)."""
     x = ef_input(grad, ef)
     if rotate:
-        x = rht_blocks(x, rademacher_signs(P.seed, rnd, 0, P.d), P.block, P.order)
+        x = rht_blocks(x, rademacher_signs(P.seed, rnd, j0, P.d), P.block, P.order)
     return x
 
 
 def uniform_range(P: Params, rnd: int, grads: Sequence[np.ndarray], efs: Optional[Sequence[np.ndarray]],
-                  rotate: bool) -> Tuple[np.ndarray, np.ndarray]:
+                  rotate: bool, j0: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     """Preliminary stage of Alg. 1: (m_k, M_k) = (min, max) over all workers of block k."""
     lo = np.full(P.K, np.inf, dtype=F32)
     hi = np.full(P.K, -np.inf, dtype=F32)
     for i in range(P.n):
-        v = uniform_values(P, rnd, grads[i], None if efs is None else efs[i], rotate).reshape(P.K, P.block)
+        v = uniform_values(P, rnd, grads[i], None if efs is None else efs[i], rotate, j0).reshape(P.K, P.block)
         lo = np.minimum(lo, v.min(axis=1))
         hi = np.maximum(hi, v.max(axis=1))
     return lo, hi
 
 
 def uniform_compress(P: Params, worker: int, rnd: int, grad: np.ndarray, ef: Optional[np.ndarray],
-                     range_m: np.ndarray, range_M: np.ndarray, rotate: bool):
+                     range_m: np.ndarray, range_M: np.ndarray, rotate: bool, j0: int = 0):
     """Main stage of Alg. 1, worker side: X_i = USQ(x_i, m, M, b), packed; with error feedback
     e' = x - D(X_i) (through RHT^-1 when rotated).  P must carry the identity table (g = 2^b - 1)."""
     assert list(P.table) == list(range(2 ** P.b)) and P.g == 2 ** P.b - 1
     x = ef_input(grad, ef)
-    v = uniform_values(P, rnd, grad, ef, rotate)
-    z = quantize_rotated(P, v, range_M, sq_halfwords(P.seed, rnd, worker, 0, P.d), range_m)
+    v = uniform_values(P, rnd, grad, ef, rotate, j0)
+    z = quantize_rotated(P, v, range_M, sq_halfwords(P.seed, rnd, worker, j0, P.d), range_m)
     new_ef = None
     if ef is not None:
         X = dequantize_indices(P, z, range_M, range_m)
         if rotate:
-            X = irht_blocks(X, rademacher_signs(P.seed, rnd, 0, P.d), P.block, P.order)
+            X = irht_blocks(X, rademacher_signs(P.seed, rnd, j0, P.d), P.block, P.order)
         new_ef = (x - X).astype(F32)
     return pack_indices(z, P.b), new_ef
 
 
 def uniform_decompress(P: Params, rnd: int, Y: np.ndarray, range_m: np.ndarray, range_M: np.ndarray,
-                       rotate: bool) -> np.ndarray:
+                       rotate: bool, j0: int = 0) -> np.ndarray:
     """Alg. 1's estimate m + (1/n) X (M-m)/(2^b-1) (then RHT^-1 when rotated); X is the integer sum."""
     _, _, step_n = block_scalars(P, range_M, range_m)
     v = ((Y.astype(F32) * np.repeat(step_n, P.block)).astype(F32) + np.repeat(range_m.astype(F32), P.block)).astype(F32)
     if rotate:
-        v = irht_blocks(v, rademacher_signs(P.seed, rnd, 0, P.d), P.block, P.order)
+        v = irht_blocks(v, rademacher_signs(P.seed, rnd, j0, P.d), P.block, P.order)
     return v
 
 

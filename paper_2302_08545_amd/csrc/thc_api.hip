@@ -151,6 +151,9 @@ size_t ws_x_bytes(const thc_params* p) { return (size_t)p->n * (size_t)p->d * si
 
 uint64_t tiles_of(uint64_t d) { return (d + TILE - 1) / TILE; }
 
+// global coordinate of the buffers' first element
+uint64_t base_coord(const thc_params* p) { return (uint64_t)p->first_block * p->block; }
+
 void fill_lut(const thc_params* p, uint32_t (&lut)[256]) {
   const uint32_t top = (1u << p->b) - 1;
   for (uint32_t k = 0; k < 256; ++k) {
@@ -327,6 +330,7 @@ int thc_prepare_range(const thc_params* p, uint64_t round, const void* const* gr
   a.ws_x = static_cast<float*>(ws);
   a.partials = reinterpret_cast<double*>(static_cast<char*>(ws) + ws_x_bytes(p));
   a.d = p->d;
+  a.j0 = base_coord(p);
   a.round = (uint32_t)round;
   a.k0 = (uint32_t)p->seed;
   a.k1 = (uint32_t)(p->seed >> 32);
@@ -388,14 +392,14 @@ int thc_compress(const thc_params* p, uint32_t worker_id, uint64_t round, const 
     q.range_M = rM;
     q.packed = pk;
     q.d = len;
-    q.j0 = j0;
+    q.j0 = base_coord(p) + j0;
     dispatch_0_7<LaunchQuant>(pl.R, q, (pl.L & 1) == 0, tiles_of(len), s);
     if (ef_inout) {
       lo.src = pk;
       lo.range_M = rM;
       hi.out = ef_inout + j0;
       hi.grad = static_cast<const char*>(grad) + j0 * in_size;
-      hi.j0 = j0;
+      hi.j0 = base_coord(p) + j0;
       // the first piece's own part of the workspace is free once its quantizer has run, and serves all later pieces
       run_inverse(p, pl, lo, wsx, hi, len, s);
     }
@@ -475,7 +479,7 @@ int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const f
     lo.src = static_cast<const uint8_t*>(agg) + j0 / 8 * p->agg_bits;
     lo.range_M = range_M + j0 / p->block;
     hi.out = out + j0;
-    hi.j0 = j0;
+    hi.j0 = base_coord(p) + j0;
     run_inverse(p, pl, lo, wsx, hi, len, s);
   }
   return check_launch();
@@ -571,6 +575,7 @@ int thc_uniform_compress(const thc_params* p, uint32_t worker_id, uint64_t round
   q.k0 = (uint32_t)p->seed;
   q.k1 = (uint32_t)(p->seed >> 32);
   q.ef_update = (!rotate && ef_inout) ? 1u : 0u;
+  q.j0 = base_coord(p);
   fill_lut(p, q.lut);
   const dim3 grid((unsigned)tiles_of(p->d)), blk(NT);
   if (p->in_dtype == THC_DTYPE_BF16) k_uniform_quant<true><<<grid, blk, 0, s>>>(q);
@@ -596,6 +601,7 @@ int thc_uniform_compress(const thc_params* p, uint32_t worker_id, uint64_t round
     hi.k1 = q.k1;
     hi.mode = 1;
     hi.bf16 = p->in_dtype == THC_DTYPE_BF16;
+    hi.j0 = base_coord(p);
     run_inverse(p, pl, lo, wsx, hi, p->d, s);
   }
   return check_launch();
@@ -632,6 +638,7 @@ int thc_uniform_decompress(const thc_params* p, uint64_t round, const void* agg,
   hi.k0 = (uint32_t)p->seed;
   hi.k1 = (uint32_t)(p->seed >> 32);
   hi.mode = 0;
+  hi.j0 = base_coord(p);
   run_inverse(p, pl, lo, wsx, hi, p->d, s);
   return check_launch();
 }

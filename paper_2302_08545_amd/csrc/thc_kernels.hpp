@@ -3,9 +3,10 @@
 // A Hadamard transform of a block of B = 2^L coordinates is split by index bits:
 //   "lo"  pass: bits [0, L1), L1 = min(L, 13): one workgroup owns 8192 consecutive coordinates
 //   "mid" pass: (only for L > 20) up to 7 more bits, in place in the workspace
-//   "hi"  pass: the remaining top bits (at most 7): one workgroup owns 2^R rows, 8192 >> R consecutive
-//               coordinates wide, rows 2^S0 coordinates apart
-// Bits are always processed in ascending order, so the rounding of every butterfly is fixed.
+//   "hi"  pass: the remaining bits (at most 7): one workgroup owns 2^R rows, 8192 >> R consecutive
+//               coordinates wide
+// Which bits each pass takes, and in which order, is fixed by the stage order (thc_params.stage_order) and
+// reaches the kernels as TileMap tables; the rounding of every butterfly is therefore fixed.
 #pragma once
 
 #include "thc_device.hpp"
@@ -23,8 +24,9 @@ struct FwdLoArgs {
   float* ws_x;         // n * d floats
   double* partials;    // n * (d >> min(L, 13)) doubles
   uint64_t d;
+  uint64_t j0;         // global coordinate of the vectors' first element (a multiple of B): indexes the diagonal
   uint32_t round, k0, k1;
-  TileMap tm;          // only `fixed` is used: the tile shape is a template parameter
+  TileMap tm;          // where the bits of the tile index land; the tile shape is a template parameter
 };
 
 // Tile index -> offset inside the tile's span for the "lo" passes.  XO = false: 8192 consecutive
@@ -78,7 +80,7 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
   }
 
   if (t < 64) {   // the tile's 8192 diagonal entries: 64 Philox calls of 128 bits
-    const uint64_t q = (off + lo_map<XO>(128u * t)) >> 7;
+    const uint64_t q = (a.j0 + off + lo_map<XO>(128u * t)) >> 7;
     const uint4 r = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, SIGN_STREAM, a.k0, a.k1);
     *reinterpret_cast<uint4*>(&sgn[4 * t]) = r;
   }
@@ -899,6 +901,7 @@ struct UQuantArgs {
   uint32_t L, b, g;
   uint32_t round, worker, k0, k1;
   uint32_t ef_update;
+  uint64_t j0;             // global coordinate of the first element
   uint32_t lut[256];
 };
 
@@ -944,7 +947,7 @@ __global__ __launch_bounds__(NT) void k_uniform_quant(const UQuantArgs a) {
     const float hv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
     const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
     const QuantScalars s{sM[bt], sLo[bt], sScale[bt], 1.0f};
-    const uint64_t q = j >> 3;
+    const uint64_t q = (a.j0 + j) >> 3;
     const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, a.worker, a.k0, a.k1);
     uint32_t z[8];
     quantize8<true>(hv, rnd, s, lut, z);          // no scaling: the values are final

@@ -33,12 +33,13 @@ def table_for(b, g, p=1 / 32):
     return o.solve_table(b, g, p)
 
 
-def both_params(d, block, n, b=4, g=30, agg_bits=8, p=1 / 32, bf16=False, seed=SEED, table=None, order=0):
+def both_params(d, block, n, b=4, g=30, agg_bits=8, p=1 / 32, bf16=False, seed=SEED, table=None, order=0,
+                first_block=0):
     T = table if table is not None else table_for(b, g, p)
     tp = o.t_p_of(p)
     P = o.Params(d=d, block=block, n=n, b=b, g=g, t_p=tp, seed=seed, table=T, agg_bits=agg_bits, order=order)
     L = api.make_params(d, block, n, b, g, tp, seed, T, agg_bits, api.THC_DTYPE_BF16 if bf16 else api.THC_DTYPE_F32,
-                        order)
+                        order, first_block)
     return P, L
 
 
@@ -375,6 +376,70 @@ def test_largest_block_against_closed_forms(order):
     out = R.out
     assert float(out[0].cpu()) == float(want0) and float(out[k1].cpu()) == float(want1)
     assert int(torch.count_nonzero(out).cpu()) == 2
+
+
+# ----------------------------------------------------------------------------- slices of a longer vector
+@pytest.mark.parametrize("first_block,block,K,n,ef,order", [(5, 1 << 12, 3, 2, True, 0), (1 << 25, 1 << 10, 4, 2, False, 0),
+                                                            (3, 1 << 16, 2, 2, True, 1), (4000, 1 << 21, 1, 1, True, 1)])
+def test_buffers_that_hold_a_slice_of_a_longer_vector(first_block, block, K, n, ef, order):
+    """thc_params.first_block: the random streams are indexed by the coordinate's position in the whole vector
+    (also beyond 2^32), so a shard computes what the whole-vector call computes for its blocks."""
+    d, j0 = block * K, first_block * block
+    P, L = both_params(d, block, n, order=order, first_block=first_block)
+    R = GpuRound(L, ef=ef)
+    grads = make_grads(d, n, seed=first_block % 1000)
+    dg = [x.to(DEV) for x in grads]
+    gn = [to_np32(x) for x in grads]
+    efs_ref = None
+    if ef:
+        efs_ref = [to_np32(torch.randn(d, generator=torch.Generator().manual_seed(9 + i)) * 1e-4) for i in range(n)]
+        for i in range(n):
+            R.efs[i].copy_(torch.from_numpy(efs_ref[i]))
+    M_ref = o.prepare_range(P, gn, efs_ref)
+    R.prepare(7, dg)
+    R.compress_all(7, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+    pks = []
+    for i in range(n):
+        pk, ne = o.compress(P, i, 7, gn[i], None if efs_ref is None else efs_ref[i], M_ref, j0=j0)
+        assert_indices_match(R.packed[i].cpu().numpy(), pk, 4, f"worker {i}")
+        if ef:
+            assert rel_l2(R.efs[i].cpu().numpy(), ne) <= 1e-5
+        R.packed[i].copy_(torch.from_numpy(pk))
+        pks.append(pk)
+    R.aggregate()
+    R.decompress(7, range_M=torch.from_numpy(M_ref).to(DEV))
+    assert rel_l2(R.out.cpu().numpy(), o.decompress(P, 7, o.aggregate(P, pks), M_ref, j0=j0)) <= 1e-5
+
+
+def test_two_slices_reproduce_the_whole_vector_bit_for_bit():
+    block, K, n, cut = 1 << 13, 6, 2, 2
+    d = block * K
+    _, Lw = both_params(d, block, n)
+    grads = [x.to(DEV) for x in make_grads(d, n, seed=77)]
+    ef0 = [(torch.randn(d, generator=torch.Generator().manual_seed(i)) * 1e-4).to(DEV) for i in range(n)]
+    W = GpuRound(Lw, ef=True)
+    for i in range(n):
+        W.efs[i].copy_(ef0[i])
+    W.prepare(2, grads)
+    W.compress_all(2, grads)
+    W.aggregate()
+    W.decompress(2)
+    for lo, hi in ((0, cut), (cut, K)):
+        a, b = lo * block, hi * block
+        _, Ls = both_params(b - a, block, n, first_block=lo)
+        S = GpuRound(Ls, ef=True)
+        for i in range(n):
+            S.efs[i].copy_(ef0[i][a:b])
+        gs = [g[a:b] for g in grads]
+        S.prepare(2, gs)
+        S.compress_all(2, gs)
+        S.aggregate()
+        S.decompress(2)
+        assert torch.equal(S.range_M, W.range_M[lo:hi])
+        for i in range(n):
+            assert torch.equal(S.packed[i], W.packed[i][a // 2:b // 2])
+            assert torch.equal(S.efs[i], W.efs[i][a:b])
+        assert torch.equal(S.agg, W.agg[a:b]) and torch.equal(S.out, W.out[a:b])
 
 
 # ----------------------------------------------------------------------------- degenerate cases

@@ -12,21 +12,23 @@ pytestmark = pytest.mark.gpu
 F32 = np.float32
 
 
-def uparams(d, block, n, b, agg_bits, bf16=False):
+def uparams(d, block, n, b, agg_bits, bf16=False, first_block=0):
     T = list(range(2 ** b))
     P = o.Params(d=d, block=block, n=n, b=b, g=2 ** b - 1, t_p=1.0, seed=SEED, table=T, agg_bits=agg_bits)
     L = api.make_params(d, block, n, b, 2 ** b - 1, 1.0, SEED, T, agg_bits,
-                        api.THC_DTYPE_BF16 if bf16 else api.THC_DTYPE_F32)
+                        api.THC_DTYPE_BF16 if bf16 else api.THC_DTYPE_F32, first_block=first_block)
     return P, L
 
 
 @pytest.mark.parametrize("rotate", [False, True], ids=["plain", "rotated"])
-@pytest.mark.parametrize("block,K,n,b,agg_bits,ef", [(1 << 10, 5, 3, 4, 8, False), (1 << 12, 2, 4, 2, 4, True),
-                                                     (1 << 14, 2, 8, 4, 7, False), (1 << 16, 1, 2, 8, 9, True),
-                                                     (1 << 20, 1, 3, 1, 2, False), (1 << 21, 1, 2, 3, 4, True)])
-def test_uniform_round(block, K, n, b, agg_bits, ef, rotate):
+@pytest.mark.parametrize("block,K,n,b,agg_bits,ef,first_block", [
+    (1 << 10, 5, 3, 4, 8, False, 0), (1 << 12, 2, 4, 2, 4, True, 0), (1 << 14, 2, 8, 4, 7, False, 0),
+    (1 << 16, 1, 2, 8, 9, True, 0), (1 << 20, 1, 3, 1, 2, False, 0), (1 << 21, 1, 2, 3, 4, True, 0),
+    (1 << 12, 3, 2, 4, 8, True, (1 << 22) + 3)])
+def test_uniform_round(block, K, n, b, agg_bits, ef, first_block, rotate):
     d = block * K
-    P, L = uparams(d, block, n, b, agg_bits)
+    j0 = first_block * block            # the buffers hold a slice of a longer vector
+    P, L = uparams(d, block, n, b, agg_bits, first_block=first_block)
     grads = make_grads(d, n, seed=block % 97 + b)
     for i, g in enumerate(grads):
         g += 0.002 * (i - 1)                                      # asymmetric ranges: m != -M
@@ -43,13 +45,13 @@ def test_uniform_round(block, K, n, b, agg_bits, ef, rotate):
     out = torch.zeros(d, dtype=torch.float32, device=DEV)
     rnd = 3
     api.thc_uniform_prepare_range(L, rnd, dg, defs, rotate, rm, rM, ws)
-    m_ref, M_ref = o.uniform_range(P, rnd, gn, efs0, rotate)
+    m_ref, M_ref = o.uniform_range(P, rnd, gn, efs0, rotate, j0)
     # minima and maxima are order-independent: the range is bit-exact, rotated or not
     assert np.array_equal(rm.cpu().numpy(), m_ref) and np.array_equal(rM.cpu().numpy(), M_ref)
     packed_ref = []
     for i in range(n):
         api.thc_uniform_compress(L, i, rnd, dg[i], None if defs is None else defs[i], rotate, rm, rM, packed[i], ws)
-        pk, ne = o.uniform_compress(P, i, rnd, gn[i], None if efs0 is None else efs0[i], m_ref, M_ref, rotate)
+        pk, ne = o.uniform_compress(P, i, rnd, gn[i], None if efs0 is None else efs0[i], m_ref, M_ref, rotate, j0)
         assert_indices_match(packed[i].cpu().numpy(), pk, b, f"worker {i}")
         packed_ref.append(pk)
         if ef:
@@ -58,7 +60,7 @@ def test_uniform_round(block, K, n, b, agg_bits, ef, rotate):
     Y = o.aggregate(P, packed_ref)
     assert np.array_equal(agg.cpu().numpy(), o.aggregate_stream(P, Y))
     api.thc_uniform_decompress(L, rnd, agg, rotate, rm, rM, out, ws)
-    ref = o.uniform_decompress(P, rnd, Y, m_ref, M_ref, rotate)
+    ref = o.uniform_decompress(P, rnd, Y, m_ref, M_ref, rotate, j0)
     assert rel_l2(out.cpu().numpy(), ref) <= 1e-5
 
 
