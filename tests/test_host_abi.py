@@ -33,11 +33,30 @@ def test_library_exports_every_declared_symbol():
     assert api.thc_strerror(0) == "THC_OK" and api.thc_strerror(-2) == "THC_ETABLE"
 
 
-def test_params_struct_layout_matches_header():
-    # d, block (8+8) n b g agg_bits in_dtype t_p (6*4) seed (8) table (256) = 304 bytes, no padding surprises
+def test_params_struct_layout_matches_header(tmp_path):
+    # d, block (8+8) n b g agg_bits in_dtype t_p (6*4) seed (8) table (256) stage_order first_block (2*4) = 312 bytes
     import ctypes
+    import shutil
+    import subprocess
     assert ctypes.sizeof(api.thc_params) == 312
     assert api.thc_params.seed.offset == 40 and api.thc_params.table.offset == 48
+    # the header is plain C: compile it with gcc and compare every field's offset with the binding's
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    fields = [f[0] for f in api.thc_params._fields_]
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "thc.h"\nint main(void) {\n'
+                   + "".join(f'  printf("{f} %zu\\n", offsetof(thc_params, {f}));\n' for f in fields)
+                   + '  printf("sizeof %zu\\n", sizeof(thc_params));\n  return 0;\n}\n')
+    exe = tmp_path / "layout"
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o",
+                    str(exe)], check=True)
+    out = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True,
+                                                       text=True).stdout.splitlines())
+    for f in fields:
+        assert int(out[f]) == getattr(api.thc_params, f).offset, f
+    assert int(out["sizeof"]) == ctypes.sizeof(api.thc_params)
 
 
 def test_workspace_size():
