@@ -157,6 +157,10 @@ def main():
         "effective_hbm_GBps": bpc * w.d / (dt / args.steps) / 1e9,
         "effective_hbm_frac": bpc * w.d / (dt / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "compulsory_bytes_per_coord": bpc,
+        # what the two-pass transforms really move (equal to the rocprofv3 counters on c3_vgg16), over the same time
+        "moved_bytes_per_coord": wl.moved_bytes_per_coord(w),
+        "moved_hbm_GBps": wl.moved_bytes_per_coord(w) * w.d / (dt / args.steps) / 1e9,
+        "moved_hbm_frac": wl.moved_bytes_per_coord(w) * w.d / (dt / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "stage_ms": stage_ms,
         "roofline": {"bound": "hbm", "kernel": "k_fwd_lo (thc_prepare_range)", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,

@@ -1,5 +1,5 @@
 """Parity of the HIP library (through the C-ABI binding) against the CPU oracle, element by element,
-on the same seeded inputs.  Bars (written here, derived in the design doc):
+on the same seeded inputs.  Bars:
   * packed bytes, aggregated sums: bit-exact, except that at most 1e-6 of the indices may differ, by one
     level, where a value sits within an ulp of a rounding threshold (expected: none);
   * float outputs (decompressed average, error-feedback buffers): relative L2 error <= 1e-5
