@@ -378,6 +378,53 @@ def test_largest_block_against_closed_forms(order):
     assert int(torch.count_nonzero(out).cpu()) == 2
 
 
+def test_a_round_captured_in_a_hip_graph_replays_bit_for_bit():
+    """The four calls only launch kernels on the caller's stream (no allocation, no memset, no host sync), so a
+    whole round can be captured once and replayed; every replay must equal the eager result, also after other
+    eager work and synchronizations in between."""
+    block, K, n = 1 << 16, 3, 4
+    d = block * K
+    _, L = both_params(d, block, n, order=1)
+    grads = [x.to(DEV) for x in make_grads(d, n, seed=5)]
+    E = GpuRound(L, ef=True)
+    E.prepare(4, grads)
+    E.compress_all(4, grads)
+    E.aggregate()
+    E.decompress(4)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (E.range_M, E.agg, E.out, *E.packed, *E.efs)]
+
+    G = GpuRound(L, ef=True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        G.prepare(4, grads)                       # warm-up on the capture stream
+        torch.cuda.synchronize()
+        for e in G.efs:
+            e.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            G.prepare(4, grads)
+            G.compress_all(4, grads)
+            G.aggregate()
+            G.decompress(4)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for e in G.efs:
+            e.zero_()                             # the round updates the error-feedback buffers in place
+        for t in (G.range_M, G.agg, G.out, *G.packed):
+            t.fill_(0)
+        scratch = torch.randn(1 << 20, device=DEV).sum()   # unrelated eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [G.range_M, G.agg, G.out, *G.packed, *G.efs]
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), f"replay {rep}"
+        del scratch
+
+
 # ----------------------------------------------------------------------------- slices of a longer vector
 @pytest.mark.parametrize("first_block,block,K,n,ef,order", [(5, 1 << 12, 3, 2, True, 0), (1 << 25, 1 << 10, 4, 2, False, 0),
                                                             (3, 1 << 16, 2, 2, True, 1), (4000, 1 << 21, 1, 1, True, 1)])
