@@ -393,26 +393,26 @@ __device__ __forceinline__ void quantize8(const float (&hv)[8], const uint4 rnd,
   }
 }
 
+// eight B-bit fields, field 0 in the least significant bits
+template <int B>
+__device__ __forceinline__ uint32_t pack8(const uint32_t (&z)[8]) {
+  uint32_t w = z[7];
+#pragma unroll
+  for (int e = 6; e >= 0; --e) w = (w << B) | z[e];
+  return w;
+}
+
 __device__ __forceinline__ void store_packed8(uint8_t* packed, uint64_t j, uint32_t b, const uint32_t (&z)[8]) {
   if (b == 4) {
-    uint32_t w = 0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) w |= z[e] << (4 * e);
-    *reinterpret_cast<uint32_t*>(packed + (j >> 1)) = w;
+    *reinterpret_cast<uint32_t*>(packed + (j >> 1)) = pack8<4>(z);
   } else if (b == 2) {
-    uint32_t w = 0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) w |= z[e] << (2 * e);
-    *reinterpret_cast<uint16_t*>(packed + (j >> 2)) = (uint16_t)w;
+    *reinterpret_cast<uint16_t*>(packed + (j >> 2)) = (uint16_t)pack8<2>(z);
   } else if (b == 8) {
     const uint32_t w0 = z[0] | z[1] << 8 | z[2] << 16 | z[3] << 24;
     const uint32_t w1 = z[4] | z[5] << 8 | z[6] << 16 | z[7] << 24;
     *reinterpret_cast<uint2*>(packed + j) = make_uint2(w0, w1);
   } else if (b == 1) {
-    uint32_t w = 0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) w |= z[e] << e;
-    packed[j >> 3] = (uint8_t)w;
+    packed[j >> 3] = (uint8_t)pack8<1>(z);
   } else {
     store_fields8(packed + (j >> 3) * b, z, b);
   }
