@@ -55,6 +55,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stage-order", choices=("ascending", "split"), default="split",
                     help="order of the butterfly stages (thc_params.stage_order)")
+    ap.add_argument("--variant", choices=("thc", "uniform", "uniform-rotated"), default="thc",
+                    help="thc: Alg. 3 (the headline).  uniform / uniform-rotated: Alg. 1 on the same workload "
+                         "(identity table, g = 2^b - 1, min/max ranges), without / with the rotation")
+    ap.add_argument("--agg-bits", type=int, default=0, help="override the width of the aggregated sums (1..16)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device-to-device copy five times and exit (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -82,6 +86,13 @@ def main():
     if args.blocks:
         w = wl.shrink(w, args.blocks)
     table, t_p = wl.table_and_threshold(w)
+    uniform = args.variant != "thc"
+    rotate = args.variant == "uniform-rotated"
+    if uniform:
+        w = wl.replace(w, g=2 ** w.b - 1)
+        table = list(range(2 ** w.b))
+    if args.agg_bits:
+        w = wl.replace(w, agg_bits=args.agg_bits)
     seed = wl.RHT_SEED
     order = api.THC_ORDER_SPLIT if args.stage_order == "split" else api.THC_ORDER_ASCENDING
     L = api.make_params(w.d, w.block, w.n, w.b, w.g, t_p, seed, table, w.agg_bits,
@@ -91,6 +102,7 @@ def main():
     efs = [torch.zeros(w.d, dtype=torch.float32, device=dev) for _ in range(w.n)] if w.ef else None
     ws = torch.empty(api.thc_workspace_bytes(L), dtype=torch.uint8, device=dev)
     range_M = torch.zeros(w.K, dtype=torch.float32, device=dev)
+    range_m = torch.zeros(w.K, dtype=torch.float32, device=dev)
     packed = [torch.zeros(w.d * w.b // 8, dtype=torch.uint8, device=dev) for _ in range(w.n)]
     agg = torch.zeros(w.d * w.agg_bits // 8, dtype=torch.uint8, device=dev)
     out = torch.zeros(w.d, dtype=torch.float32, device=dev)
@@ -103,17 +115,27 @@ def main():
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)] if timed else None
         if timed:
             ev[0].record()
-        api.thc_prepare_range(L, rnd, grads, efs, range_M, ws)
+        if uniform:
+            api.thc_uniform_prepare_range(L, rnd, grads, efs, rotate, range_m, range_M, ws)
+        else:
+            api.thc_prepare_range(L, rnd, grads, efs, range_M, ws)
         if timed:
             ev[1].record()
         for i in range(w.n):
-            api.thc_compress(L, i, rnd, grads[i], None if efs is None else efs[i], range_M, packed[i], ws)
+            ef_i = None if efs is None else efs[i]
+            if uniform:
+                api.thc_uniform_compress(L, i, rnd, grads[i], ef_i, rotate, range_m, range_M, packed[i], ws)
+            else:
+                api.thc_compress(L, i, rnd, grads[i], ef_i, range_M, packed[i], ws)
         if timed:
             ev[2].record()
         api.thc_aggregate(L, packed, agg)
         if timed:
             ev[3].record()
-        api.thc_decompress(L, rnd, agg, range_M, out, ws)
+        if uniform:
+            api.thc_uniform_decompress(L, rnd, agg, rotate, range_m, range_M, out, ws)
+        else:
+            api.thc_decompress(L, rnd, agg, range_M, out, ws)
         if timed:
             ev[4].record()
             events.append(ev)
@@ -152,7 +174,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "d_padded": w.d, "d_real": w.real, "rht_block": w.block, "workers": w.n,
                    "b": w.b, "g": w.g, "agg_bits": w.agg_bits, "error_feedback": w.ef, "input": w.dtype,
-                   "stage_order": args.stage_order},
+                   "stage_order": args.stage_order, "variant": args.variant},
         "worker_coords_per_s": w.n * w.d / (dt / args.steps),
         "effective_hbm_GBps": bpc * w.d / (dt / args.steps) / 1e9,
         "effective_hbm_frac": bpc * w.d / (dt / args.steps) / 1e9 / HBM_PEAK_GBPS,
@@ -166,7 +188,11 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "algorithmic_bytes": lo_alg_bytes, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
     }
-    if not args.no_cpu_baseline:
+    if uniform:
+        # Alg. 1 runs other kernels: the figures above that describe Alg. 3's passes do not apply
+        for key in ("roofline", "moved_bytes_per_coord", "moved_hbm_GBps", "moved_hbm_frac"):
+            result[key] = None
+    elif not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, table, t_p, seed, order)
     print(json.dumps(result), flush=True)
 
