@@ -489,6 +489,58 @@ def test_two_slices_reproduce_the_whole_vector_bit_for_bit():
         assert torch.equal(S.agg, W.agg[a:b]) and torch.equal(S.out, W.out[a:b])
 
 
+def _random_configurations(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        L = int(rng.integers(10, 18))
+        K = int(rng.integers(1, 5))
+        n = int(rng.integers(1, 7))
+        b = int(rng.integers(1, 9))
+        g = int(rng.integers(2 ** b - 1, min(255, 4 * 2 ** b) + 1))
+        need = int(np.ceil(np.log2(g * n + 1)))
+        agg_bits = int(rng.choice([need, 8, 16, int(rng.integers(need, 17))]))
+        agg_bits = max(agg_bits, need)
+        out.append((L, K, n, b, g, agg_bits, bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), int(rng.integers(0, 2)),
+                    int(rng.choice([0, 0, 7, 1 << 23]))))
+    return out
+
+
+@pytest.mark.parametrize("L,K,n,b,g,agg_bits,ef,bf16,order,first_block", _random_configurations(16, 20230208))
+def test_seeded_random_configurations(L, K, n, b, g, agg_bits, ef, bf16, order, first_block):
+    """Valid parameter combinations drawn from a fixed seed: block size, worker count, index and sum widths,
+    granularity (with the oracle's optimal table for it), error feedback, bf16 input, stage order, slice offset."""
+    block = 1 << L
+    d, j0 = block * K, first_block * block
+    P, Lp = both_params(d, block, n, b=b, g=g, agg_bits=agg_bits, bf16=bf16, order=order, first_block=first_block)
+    R = GpuRound(Lp, ef=ef)
+    grads = make_grads(d, n, seed=L * 100 + K, bf16=bf16)
+    dg = [x.to(DEV) for x in grads]
+    gn = [to_np32(x) for x in grads]
+    efs_ref = None
+    if ef:
+        efs_ref = [to_np32(torch.randn(d, generator=torch.Generator().manual_seed(i)) * 2e-4) for i in range(n)]
+        for i in range(n):
+            R.efs[i].copy_(torch.from_numpy(efs_ref[i]))
+    M_ref = o.prepare_range(P, gn, efs_ref)
+    R.prepare(5, dg)
+    assert np.all(np.abs(R.range_M.cpu().numpy() - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
+    R.compress_all(5, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+    pks = []
+    for i in range(n):
+        pk, ne = o.compress(P, i, 5, gn[i], None if efs_ref is None else efs_ref[i], M_ref, j0=j0)
+        assert_indices_match(R.packed[i].cpu().numpy(), pk, b, f"worker {i}")
+        if ef:
+            assert rel_l2(R.efs[i].cpu().numpy(), ne) <= 1e-5
+        R.packed[i].copy_(torch.from_numpy(pk))
+        pks.append(pk)
+    R.aggregate()
+    Y = o.aggregate(P, pks)
+    assert np.array_equal(R.agg.cpu().numpy(), o.aggregate_stream(P, Y))
+    R.decompress(5, range_M=torch.from_numpy(M_ref).to(DEV))
+    assert rel_l2(R.out.cpu().numpy(), o.decompress(P, 5, Y, M_ref, j0=j0)) <= 1e-5
+
+
 # ----------------------------------------------------------------------------- degenerate cases
 def test_all_zero_block_and_zero_padding():
     block, K, n = 1 << 12, 3, 2
