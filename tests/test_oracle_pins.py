@@ -598,3 +598,29 @@ def test_solver_special_cases():
     assert o.solve_table(2, 8, 1 / 32) == [0, 3, 5, 8]
     # finer grids never hurt when they refine the coarse grid
     assert o.table_cost(o.solve_table(4, 30, 1 / 32), 30, TP32) <= o.table_cost(list(range(16)), 15, TP32)
+
+
+def test_a_slice_with_its_offset_reproduces_the_whole_vector():
+    """Blocks are independent instances and the random streams are indexed by global coordinate: compressing and
+    decompressing blocks [2, 5) on their own, with j0 = 2 B, gives the bytes of the whole-vector result."""
+    B, K, n = 1024, 5, 3
+    P = _params(d=B * K, block=B, n=n)
+    rng = np.random.default_rng(11)
+    grads = [rng.standard_normal(P.d).astype(np.float32) * 1e-3 for _ in range(n)]
+    efs = [rng.standard_normal(P.d).astype(np.float32) * 1e-4 for _ in range(n)]
+    M, packed, Y, out, new_efs = o.thc_round(P, 4, grads, efs)
+    lo, hi = 2 * B, 5 * B
+    Ps = _params(d=hi - lo, block=B, n=n)
+    Ms = o.prepare_range(Ps, [g[lo:hi] for g in grads], [e[lo:hi] for e in efs])
+    assert np.array_equal(Ms, M[2:5])
+    pks = []
+    for i in range(n):
+        pk, ne = o.compress(Ps, i, 4, grads[i][lo:hi], efs[i][lo:hi], Ms, j0=lo)
+        assert np.array_equal(pk, packed[i][lo // 2:hi // 2]) and np.array_equal(ne, new_efs[i][lo:hi])
+        pks.append(pk)
+    Ys = o.aggregate(Ps, pks)
+    assert np.array_equal(Ys, Y[lo:hi])
+    assert np.array_equal(o.decompress(Ps, 4, Ys, Ms, j0=lo), out[lo:hi])
+    # and the offset matters: the same slice taken for the start of a vector uses other random draws
+    pk0, _ = o.compress(Ps, 0, 4, grads[0][lo:hi], efs[0][lo:hi], Ms, j0=0)
+    assert not np.array_equal(pk0, pks[0])
