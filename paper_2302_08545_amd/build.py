@@ -8,7 +8,7 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 LIB_PATH = os.path.join(PKG_DIR, "libthc.so")
-SOURCES = [os.path.join(PKG_DIR, "csrc", "thc_api.hip")]
+SOURCES = [os.path.join(PKG_DIR, "csrc", "thc_api.hip"), os.path.join(PKG_DIR, "csrc", "thc_tables.cpp")]
 
 HIPCC_FLAGS = [
     "-shared", "-fPIC", "-O3", "-std=c++17",

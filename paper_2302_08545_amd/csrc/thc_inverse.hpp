@@ -1,0 +1,203 @@
+// Inverse transform passes: decompression and the error-feedback update (Alg. 2 / Alg. 3).
+#pragma once
+
+#include "thc_forward.hpp"
+
+namespace thc {
+
+// ---------------------------------------------------------------------------------------------
+// Sixteen consecutive codes (table indices or aggregated sums) of `bits` bits each, starting at
+// coordinate j (a multiple of 16): codes_load fetches the raw words (for the widths with a fast path)
+// or the decoded fields (any other width); codes_decode finishes the fast paths.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void codes_load(const uint8_t* s8, uint32_t bits, uint64_t j, uint32_t (&w)[8],
+                                           uint32_t (&y)[16]) {
+  if (bits == 8) {
+    const uint4 r = *reinterpret_cast<const uint4*>(s8 + j);
+    w[0] = r.x; w[1] = r.y; w[2] = r.z; w[3] = r.w;
+  } else if (bits == 16) {
+    const uint4 r0 = *reinterpret_cast<const uint4*>(s8 + 2 * j);
+    const uint4 r1 = *reinterpret_cast<const uint4*>(s8 + 2 * j + 16);
+    w[0] = r0.x; w[1] = r0.y; w[2] = r0.z; w[3] = r0.w; w[4] = r1.x; w[5] = r1.y; w[6] = r1.z; w[7] = r1.w;
+  } else if (bits == 4) {
+    const uint2 r = *reinterpret_cast<const uint2*>(s8 + (j >> 1));
+    w[0] = r.x; w[1] = r.y;
+  } else if (bits == 2) {
+    w[0] = *reinterpret_cast<const uint32_t*>(s8 + (j >> 2));
+  } else if (bits == 1) {
+    w[0] = *reinterpret_cast<const uint16_t*>(s8 + (j >> 3));
+  } else {   // any other width: eight fields take `bits` bytes
+    uint32_t z0[8], z1[8];
+    load_fields8(s8 + (j >> 3) * bits, bits, z0);
+    load_fields8(s8 + ((j >> 3) + 1) * bits, bits, z1);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { y[e] = z0[e]; y[8 + e] = z1[e]; }
+  }
+}
+
+__device__ __forceinline__ void codes_decode(uint32_t bits, bool ok, const uint32_t (&w)[8], uint32_t (&y)[16]) {
+  if (bits == 8) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 2] >> (8 * (e & 3))) & 255u;
+  } else if (bits == 16) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+  } else if (bits == 4) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 3] >> (4 * (e & 7))) & 15u;
+  } else if (bits == 2) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[0] >> (2 * e)) & 3u;
+  } else if (bits == 1) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (w[0] >> e) & 1u;
+  } else if (!ok) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = 0;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Inverse "lo" pass.  Source is either the aggregated stream (decompression, Alg. 2:
+// m + (Y/n)(M-m)/g = Y * step_n - M) or one worker's packed indices (error feedback, Alg. 3:
+// X_i = m + T[z](M-m)/g = T[z] * step_g - M).  One thread loads 16 consecutive coordinates.
+// ---------------------------------------------------------------------------------------------
+struct InvLoArgs {
+  const void* src;         // aggregated stream or packed indices
+  const float* range_M;
+  const float* range_m;    // or null: m = -M
+  float* ws_x;             // d floats, written
+  uint64_t d;
+  uint32_t L;
+  uint32_t src_bits;       // bits per coordinate in src
+  uint32_t use_table;      // 1: src holds table indices; 0: src holds aggregated table values
+  uint32_t divisor;        // g*n (aggregated) or g (indices)
+  TileMap tm;
+  uint8_t table[256];
+};
+
+template <int L1, bool XO>
+__global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
+  static_assert(!XO || L1 == LOG_TILE, "the row-split tile needs blocks of at least 2^16");
+  constexpr bool GUARD = L1 < LOG_TILE;
+  __shared__ __align__(16) float lds[TILE];
+  __shared__ float sM[8], sStep[8];
+  __shared__ float tabf[256];
+
+  const int t = threadIdx.x;
+  const uint64_t off = tm_base(a.tm, blockIdx.x);
+  const int idx = 16 * t;
+  const uint64_t j = off + lo_map<XO>(idx);
+  const bool ok = !GUARD || j < a.d;
+
+  // raw bits first, so the load is in flight while the block constants are prepared
+  uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  uint32_t y[16];
+  if (ok) codes_load(static_cast<const uint8_t*>(a.src), a.src_bits, j, w, y);
+
+  const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
+  if (t < nblk) {
+    const uint64_t blk = (off >> a.L) + t;
+    float M = 0.f, m = 0.f;
+    if (blk < (a.d >> a.L)) { M = a.range_M[blk]; m = lower_of(a.range_m, blk, M); }
+    sM[t] = m;                                                   // the affine map only needs the lower end
+    sStep[t] = (float)(((double)M - (double)m) / (double)a.divisor);
+  }
+  if (a.use_table && t < 256) tabf[t] = (float)a.table[t];
+  __syncthreads();
+
+  codes_decode(a.src_bits, ok, w, y);
+  const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
+  const float lo = sM[bt], step = sStep[bt];
+  float v[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    const float f = a.use_table ? tabf[y[e]] : (float)y[e];
+    v[e] = ok ? f * step + lo : 0.f;
+  }
+  bfly<4>(v);
+#pragma unroll
+  for (int e = 0; e < 16; e += 4)
+    *reinterpret_cast<float4*>(&lds[swz(idx + e)]) = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
+
+  float* dst = a.ws_x + off;
+  const uint64_t left = a.d - off;
+  lds_stages<4, L1, true, SWZ>(lds, t, [&](int base, int eoff, float val) {
+    if (!GUARD || (uint64_t)(base + eoff) < left) dst[lo_map<XO>(base) + lo_map<XO>(eoff)] = val;
+  });
+}
+
+// ---------------------------------------------------------------------------------------------
+// Inverse "hi" pass: finish H, scale by 1/sqrt(B), apply the diagonal (Sec. 5.1: RHT^-1 = D H / sqrt(d)).
+// mode 0: out = result (Alg. 3, the global update);
+// mode 1: e <- (grad + e) - result (Alg. 3, error-feedback update), out = ef buffer, read and written.
+// ---------------------------------------------------------------------------------------------
+struct InvHiArgs {
+  const float* x;      // half-rotated vector, d floats
+  float* out;          // d floats
+  const void* grad;    // mode 1 only
+  uint64_t d;
+  uint64_t j0;         // global coordinate of x[0] (a multiple of B), for the diagonal's random stream
+  TileMap tm;
+  uint32_t round, k0, k1;
+  uint32_t mode, bf16;
+  float c;
+};
+
+__device__ __forceinline__ float4 inv_finish4(float4 v, uint32_t bits, const InvHiArgs& a, uint64_t j) {
+  v.x = flip(v.x * a.c, bits & 1u);
+  v.y = flip(v.y * a.c, (bits >> 1) & 1u);
+  v.z = flip(v.z * a.c, (bits >> 2) & 1u);
+  v.w = flip(v.w * a.c, (bits >> 3) & 1u);
+  if (a.mode == 1) {
+    float4 x = a.bf16 ? load_grad4<true>(a.grad, j) : load_grad4<false>(a.grad, j);
+    const float4 e = *reinterpret_cast<const float4*>(a.out + j);
+    x.x += e.x; x.y += e.y; x.z += e.z; x.w += e.w;
+    v = make_float4(x.x - v.x, x.y - v.y, x.z - v.z, x.w - v.w);
+  }
+  return v;
+}
+
+template <int R>
+__global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
+  __shared__ __align__(16) float lds[TILE];
+  __shared__ uint32_t sgn[TILE / 32];
+
+  const int t = threadIdx.x;
+  const HiGeom<R> g(blockIdx.x, a.tm);
+
+  if constexpr (R >= 2) {
+    hi_front<R>(a.x, g, lds, t);
+    // 32 consecutive tile indices are 32 consecutive coordinates (rows are at least 64 wide)
+    if (t < TILE / 32) sgn[t] = sign_word(a.j0 + g.coord(32 * t), a.round, a.k0, a.k1);
+    int idx[2];
+    float v[2][8];
+    hi_back<R>(lds, t, idx, v);
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint64_t j = g.coord(idx[h]);
+      const uint32_t bits = sgn[idx[h] >> 5] >> (idx[h] & 31);
+      const float4 o0 = inv_finish4(make_float4(v[h][0], v[h][1], v[h][2], v[h][3]), bits, a, j);
+      const float4 o1 = inv_finish4(make_float4(v[h][4], v[h][5], v[h][6], v[h][7]), bits >> 4, a, j + 4);
+      *reinterpret_cast<float4*>(a.out + j) = o0;
+      *reinterpret_cast<float4*>(a.out + j + 4) = o1;
+    }
+  } else {
+    if (t < TILE / 32) sgn[t] = sign_word(a.j0 + g.coord(32 * t), a.round, a.k0, a.k1);
+    hi_load_to_lds<R>(a.x, g, a.d, lds, t);
+    lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, int, float) {});
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int idx = 4 * (i * NT + t);
+      const uint64_t j = g.coord(idx);
+      if (j >= a.d) continue;
+      const float4 v = *reinterpret_cast<const float4*>(&lds[idx]);
+      const uint32_t bits = sgn[idx >> 5] >> (idx & 31);
+      *reinterpret_cast<float4*>(a.out + j) = inv_finish4(v, bits, a, j);
+    }
+  }
+}
+
+}  // namespace thc

@@ -7,1184 +7,15 @@
 //               coordinates wide
 // Which bits each pass takes, and in which order, is fixed by the stage order (thc_params.stage_order) and
 // reaches the kernels as TileMap tables; the rounding of every butterfly is therefore fixed.
+//
+//   thc_device.hpp     building blocks: tiling, Philox, butterflies, LDS rounds, bit-stream codec
+//   thc_forward.hpp    k_fwd_lo, k_range, k_mid, k_fwd_hi_quant
+//   thc_inverse.hpp    k_inv_lo, k_inv_hi
+//   thc_uniform.hpp    k_minmax, k_minmax_final, k_fwd_hi_store, k_uniform_quant, k_uniform_dequant
+//   thc_aggregate.hpp  k_aggregate_b4w8, k_aggregate_b4w16, k_aggregate_b2w8, k_aggregate_generic
 #pragma once
 
-#include "thc_device.hpp"
-
-namespace thc {
-
-// ---------------------------------------------------------------------------------------------
-// Forward "lo" pass (Alg. 3: x = grad + e; ||x||; first part of R = RHT(x) with the diagonal D^r).
-// grid = (tiles, n workers).  Writes the half-rotated tile to ws_x[worker] and one partial sum of
-// squares per min(B, 8192) coordinates.
-// ---------------------------------------------------------------------------------------------
-struct FwdLoArgs {
-  PtrArr grads;
-  PtrArr efs;          // unused without error feedback
-  float* ws_x;         // n * d floats
-  double* partials;    // n * (d >> min(L, 13)) doubles
-  uint64_t d;
-  uint64_t j0;         // global coordinate of the vectors' first element (a multiple of B): indexes the diagonal
-  uint32_t round, k0, k1;
-  TileMap tm;          // where the bits of the tile index land; the tile shape is a template parameter
-};
-
-// Tile index -> offset inside the tile's span for the "lo" passes.  XO = false: 8192 consecutive
-// coordinates.  XO = true: eight rows of 1024 consecutive coordinates, rows at offset bits 13..15 (the
-// workgroup's XCD then stays on one value of offset bits 10..12 for reads and writes alike).
-template <bool XO>
-__device__ __forceinline__ uint32_t lo_map(uint32_t idx) {
-  return XO ? ((idx & 1023u) | ((idx >> 10) << 13)) : idx;
-}
-
-template <bool BF16>
-__device__ __forceinline__ float4 load_grad4(const void* g, uint64_t j) {
-  if constexpr (BF16) {
-    const ushort4 h = *reinterpret_cast<const ushort4*>(static_cast<const uint16_t*>(g) + j);
-    return make_float4(bf16_to_f32(h.x), bf16_to_f32(h.y), bf16_to_f32(h.z), bf16_to_f32(h.w));
-  } else {
-    return *reinterpret_cast<const float4*>(static_cast<const float*>(g) + j);
-  }
-}
-
-// One workgroup per tile (grid = (tiles, n workers)): measured on MI355X this streams faster than a
-// persistent grid with software prefetch, the hardware dispatcher keeps four workgroups per CU in flight.
-template <int L1, bool BF16, bool EF, bool XO>
-__global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
-  static_assert(!XO || L1 == LOG_TILE, "the row-split tile needs blocks of at least 2^16");
-  // Vectors are multiples of B, so only blocks shorter than a tile can leave the last tile partial.
-  constexpr bool GUARD = L1 < LOG_TILE;
-  __shared__ __align__(16) float lds[TILE_PAD];
-  __shared__ uint32_t sgn[TILE / 32];
-  __shared__ double wsum[4][NT / 64];
-
-  const int t = threadIdx.x;
-  const uint32_t worker = blockIdx.y;
-  const void* grad = a.grads.p[worker];
-  const float* ef = EF ? static_cast<const float*>(a.efs.p[worker]) : nullptr;
-  const int wave = t >> 6, lane = t & 63;
-  const uint64_t off = tm_base(a.tm, blockIdx.x);   // coordinate of tile index 0
-
-  // all loads of the tile are issued before anything waits on them
-  float4 x[4], e[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint64_t j = off + lo_map<XO>(4u * (uint32_t)(i * NT + t));
-    const bool ok = !GUARD || j < a.d;
-    x[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    e[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (ok) {
-      x[i] = load_grad4<BF16>(grad, j);
-      if constexpr (EF) e[i] = *reinterpret_cast<const float4*>(ef + j);
-    }
-  }
-
-  if (t < 64) {   // the tile's 8192 diagonal entries: 64 Philox calls of 128 bits
-    const uint64_t q = (a.j0 + off + lo_map<XO>(128u * t)) >> 7;
-    const uint4 r = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, SIGN_STREAM, a.k0, a.k1);
-    *reinterpret_cast<uint4*>(&sgn[4 * t]) = r;
-  }
-  if constexpr (EF) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { x[i].x += e[i].x; x[i].y += e[i].y; x[i].z += e[i].z; x[i].w += e[i].w; }
-  }
-  // sum of squares in binary64 (a binary32 square is exact there)
-  double acc[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const double p = (double)x[i].x, q = (double)x[i].y, r = (double)x[i].z, s = (double)x[i].w;
-    acc[i] = __builtin_fma(s, s, __builtin_fma(r, r, __builtin_fma(q, q, p * p)));
-  }
-  // a thread's four float4 sit 2048 coordinates apart: they share a block only if the block is that large
-  if constexpr (L1 >= 13) {
-    const double s = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
-    if (lane == 0) wsum[0][wave] = s;
-  } else if constexpr (L1 == 12) {
-    const double s0 = wave_sum(acc[0] + acc[1]), s1 = wave_sum(acc[2] + acc[3]);
-    if (lane == 0) { wsum[0][wave] = s0; wsum[1][wave] = s1; }
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const double s = wave_sum(acc[i]);
-      if (lane == 0) wsum[i][wave] = s;
-    }
-  }
-  __syncthreads();   // diagonal bits and wave sums visible
-
-  // partial sums: one per block of 2^L1 coordinates inside the tile, combined in a fixed order
-  constexpr int NBLK = TILE >> L1;
-  if (t < NBLK) {
-    double s = 0.0;
-    if constexpr (L1 >= 13) {
-#pragma unroll
-      for (int w = 0; w < 8; ++w) s += wsum[0][w];
-    } else if constexpr (L1 == 12 || L1 == 11) {
-#pragma unroll
-      for (int w = 0; w < 8; ++w) s += wsum[t][w];
-    } else {   // L1 == 10: block = 2 * i + (wave >> 2)
-#pragma unroll
-      for (int w = 0; w < 4; ++w) s += wsum[t >> 1][4 * (t & 1) + w];
-    }
-    // one partial per tile (all of it in one block) or, for blocks below 8192, per block of the linear tile
-    const uint64_t pidx = L1 >= LOG_TILE ? (uint64_t)blockIdx.x : (off >> L1) + t;
-    if (pidx < (a.d >> L1)) a.partials[(uint64_t)worker * (a.d >> L1) + pidx] = s;
-  }
-
-  // diagonal, strides 1 and 2, then into LDS
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int idx = 4 * (i * NT + t);
-    const uint32_t bits = sgn[idx >> 5] >> (idx & 31);
-    x[i].x = flip(x[i].x, bits & 1u);
-    x[i].y = flip(x[i].y, (bits >> 1) & 1u);
-    x[i].z = flip(x[i].z, (bits >> 2) & 1u);
-    x[i].w = flip(x[i].w, (bits >> 3) & 1u);
-    bfly_f4(x[i]);
-    *reinterpret_cast<float4*>(&lds[phys<PAD>(idx)]) = x[i];
-  }
-
-  float* dst = a.ws_x + (uint64_t)worker * a.d + off;
-  const uint64_t left = a.d - off;   // coordinates of this tile that exist (tail tile of a short vector)
-  lds_stages<2, L1, true, PAD>(lds, t, [&](int base, int eoff, float v) {
-    if (!GUARD || (uint64_t)(base + eoff) < left) dst[lo_map<XO>(base) + lo_map<XO>(eoff)] = v;
-  });
-}
-
-// ---------------------------------------------------------------------------------------------
-// Range (Sec. 5.3; Alg. 3: M = (t_p / sqrt(d)) * max_i ||x_i||, per block).  One wave per block.
-// ---------------------------------------------------------------------------------------------
-struct RangeArgs {
-  const double* partials;   // n * (d >> L1)
-  float* range_M;           // K
-  uint64_t d;
-  uint32_t n, L, L1;
-  float t_p;
-};
-
-constexpr int RANGE_NT = 1024;
-
-// One workgroup per block: Sigma x^2 of every worker in a fixed summation order (thread-strided partial sums,
-// wave butterflies, then the 16 wave totals in sequence), the maximum over workers, and M.
-__global__ __launch_bounds__(RANGE_NT) void k_range(const RangeArgs a) {
-  __shared__ double wsum[MAXW][RANGE_NT / 64];
-  const uint64_t k = blockIdx.x;
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const uint32_t ppb = 1u << (a.L - a.L1);           // partials per block
-  const uint64_t per_worker = a.d >> a.L1;
-  for (uint32_t i = 0; i < a.n; ++i) {
-    const double* p = a.partials + (uint64_t)i * per_worker + k * ppb;
-    double s = 0.0;
-    for (uint32_t j = t; j < ppb; j += RANGE_NT) s += p[j];
-    s = wave_sum(s);
-    if (lane == 0) wsum[i][wave] = s;
-  }
-  __syncthreads();
-  if (t == 0) {
-    double smax = 0.0;
-    for (uint32_t i = 0; i < a.n; ++i) {
-      double s = 0.0;
-      for (int w = 0; w < RANGE_NT / 64; ++w) s += wsum[i][w];
-      smax = s > smax ? s : smax;
-    }
-    const double M = ((double)a.t_p * __builtin_sqrt(smax)) / __builtin_sqrt((double)(1ull << a.L));
-    a.range_M[k] = (float)M;
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Shared addressing of the strided passes: a tile of 2^R rows by W = 8192 >> R columns (see TileMap).
-// ---------------------------------------------------------------------------------------------
-template <int R>
-struct HiGeom {
-  static constexpr int LOGW = LOG_TILE - R;
-  static constexpr int W = 1 << LOGW;
-  const TileMap& m;
-  uint64_t base;   // coordinate of (row 0, col 0)
-  __device__ HiGeom(uint32_t tile, const TileMap& m_) : m(m_), base(tm_base(m_, tile)) {}
-  // offset of a tile index from `base`: 32 bits are enough (blocks are at most 2^27 coordinates), so device
-  // addresses can be formed as uniform 64-bit base + 32-bit per-lane offset
-  __device__ uint32_t off(int idx) const { return tm_row(m, (uint32_t)idx >> LOGW) + (uint32_t)(idx & (W - 1)); }
-  __device__ uint64_t coord(int idx) const { return base + off(idx); }
-};
-
-// Front half of a strided pass with R >= 2 row bits (no bounds checks: such tiles are always whole).
-// Each thread loads four rows (4 rho + 0..3) of four consecutive columns, finishes row bits 0 and 1 in
-// registers, parks the tile in LDS (row-major, no padding) and runs row bits [2, 2 + NB1) as one LDS
-// round.  What is left is NB2 = R - 2 - NB1 (0 or 1) top bits for the caller's epilogue.
-template <int R>
-struct HiSplit {
-  static constexpr int LOGW = LOG_TILE - R;
-  static constexpr int W = 1 << LOGW;
-  static constexpr int NB1 = (R - 2) < 4 ? (R - 2) : 4;
-  static constexpr int NB2 = R - 2 - NB1;
-  static_assert(R >= 2 && R <= 7 && NB2 <= 1, "strided pass handles 2..7 row bits");
-};
-
-template <int R>
-__device__ __forceinline__ void hi_issue_loads(const float* src, const HiGeom<R>& g, int t, float4 (&x)[4]) {
-  using S = HiSplit<R>;
-  const int cg = t & (S::W / 4 - 1), rho = t >> (S::LOGW - 2);
-  const float* pb = src + g.base;
-  const uint32_t o = tm_row(g.m, 4 * rho) + 4 * cg;
-  const uint32_t p1 = tm_row(g.m, 1), p2 = tm_row(g.m, 2);   // rows 4 rho + {1, 2, 3}
-  x[0] = *reinterpret_cast<const float4*>(pb + o);
-  x[1] = *reinterpret_cast<const float4*>(pb + (o + p1));
-  x[2] = *reinterpret_cast<const float4*>(pb + (o + p2));
-  x[3] = *reinterpret_cast<const float4*>(pb + (o + p1 + p2));
-}
-
-// row bits 0 and 1 in registers, then the tile goes to LDS (row-major, no padding)
-template <int R>
-__device__ __forceinline__ void hi_r0_to_lds(float4 (&x)[4], float* lds, int t) {
-  using S = HiSplit<R>;
-  const int cg = t & (S::W / 4 - 1), rho = t >> (S::LOGW - 2);
-  bf4(x[0], x[1]); bf4(x[2], x[3]);   // row bit 0
-  bf4(x[0], x[2]); bf4(x[1], x[3]);   // row bit 1
-  float* q = lds + (4 * rho) * S::W + 4 * cg;
-  *reinterpret_cast<float4*>(q) = x[0];
-  *reinterpret_cast<float4*>(q + S::W) = x[1];
-  *reinterpret_cast<float4*>(q + 2 * S::W) = x[2];
-  *reinterpret_cast<float4*>(q + 3 * S::W) = x[3];
-}
-
-// row bits [2, 2 + NB1)  <->  tile index bits [LOGW + 2, LOGW + 2 + NB1); ends with the tile readable
-template <int R>
-__device__ __forceinline__ void hi_round1(float* lds, int t) {
-  using S = HiSplit<R>;
-  lds_stages<S::LOGW + 2, S::LOGW + 2 + S::NB1, false, PLAIN>(lds, t, [](int, int, float) {});
-  __syncthreads();
-}
-
-template <int R>
-__device__ __forceinline__ void hi_front(const float* src, const HiGeom<R>& g, float* lds, int t) {
-  float4 x[4];
-  hi_issue_loads<R>(src, g, t, x);
-  hi_r0_to_lds<R>(x, lds, t);
-  hi_round1<R>(lds, t);
-}
-
-// Two groups of eight consecutive coordinates per thread, with the last row bit (if any) applied:
-// tile index of each group in idx[], values in v[][].
-template <int R>
-__device__ __forceinline__ void hi_back(const float* lds, int t, int (&idx)[2], float (&v)[2][8]) {
-  using S = HiSplit<R>;
-  if constexpr (S::NB2 == 1) {
-    const int oct = t & (S::W / 8 - 1), r = t >> (S::LOGW - 3);      // r < 2^(R-1)
-    idx[0] = r * S::W + 8 * oct;
-    idx[1] = idx[0] + (TILE >> 1);
-  } else {
-    idx[0] = 8 * t;
-    idx[1] = 8 * (t + NT);
-  }
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const float4 p0 = *reinterpret_cast<const float4*>(&lds[idx[h]]);
-    const float4 p1 = *reinterpret_cast<const float4*>(&lds[idx[h] + 4]);
-    v[h][0] = p0.x; v[h][1] = p0.y; v[h][2] = p0.z; v[h][3] = p0.w;
-    v[h][4] = p1.x; v[h][5] = p1.y; v[h][6] = p1.z; v[h][7] = p1.w;
-  }
-  if constexpr (S::NB2 == 1) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float a = v[0][e], b = v[1][e];
-      v[0][e] = a + b;
-      v[1][e] = a - b;
-    }
-  }
-}
-
-// generic (slow) front for R < 2 and partial tiles: whole transform part through LDS
-template <int R>
-__device__ __forceinline__ void hi_load_to_lds(const float* src, const HiGeom<R>& g, uint64_t d, float* lds, int t) {
-  float4 v[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint64_t j = g.coord(4 * (i * NT + t));
-    v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (j < d) v[i] = *reinterpret_cast<const float4*>(src + j);
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) *reinterpret_cast<float4*>(&lds[4 * (i * NT + t)]) = v[i];
-}
-
-// ---------------------------------------------------------------------------------------------
-// "mid" pass: R more bits, in place.
-// ---------------------------------------------------------------------------------------------
-struct MidArgs {
-  float* x;   // d floats (one worker's half-rotated vector)
-  uint64_t d;
-  TileMap tm;
-};
-
-template <int R>
-__global__ __launch_bounds__(NT) void k_mid(const MidArgs a) {
-  __shared__ __align__(16) float lds[TILE];
-  const int t = threadIdx.x;
-  const HiGeom<R> g(blockIdx.x, a.tm);
-  if constexpr (R >= 2) {
-    hi_front<R>(a.x, g, lds, t);
-    int idx[2];
-    float v[2][8];
-    hi_back<R>(lds, t, idx, v);
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      float* o = a.x + g.coord(idx[h]);
-      *reinterpret_cast<float4*>(o) = make_float4(v[h][0], v[h][1], v[h][2], v[h][3]);
-      *reinterpret_cast<float4*>(o + 4) = make_float4(v[h][4], v[h][5], v[h][6], v[h][7]);
-    }
-  } else {
-    hi_load_to_lds<R>(a.x, g, a.d, lds, t);
-    lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, int, float) {});
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int idx = 4 * (i * NT + t);
-      const uint64_t j = g.coord(idx);
-      if (j < a.d) *reinterpret_cast<float4*>(a.x + j) = *reinterpret_cast<const float4*>(&lds[idx]);
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Forward "hi" pass + main stage, worker side (Alg. 3: R = RHT(x) finished; clamp to [-M, M];
-// stochastic quantization onto the table's values (Sec. 4.1); Z = T^-1[Y] (Alg. 2); bit-pack).
-//
-// Per coordinate, in binary32:  v = h * c;  x' = med(v, -M, M);  y16 = (x' + M) * (scale * 2^16);
-// k = floor(y16 / 2^16);  (lo, wd, z0) = LUT[k];  t16 = y16 - lo * 2^16;
-// up iff (half + 1/2) * wd < t16  (one fused multiply-add, then compare);  z = z0 + up.
-// The top table entry carries wd = 255 so that it can never round up.  When 1/sqrt(B) is a power of
-// two (even log2 B) the multiplication by c is folded into M and the scale: that only moves exponents,
-// so every rounding stays where it was.
-// ---------------------------------------------------------------------------------------------
-struct QuantArgs {
-  const float* x;          // one worker's half-rotated vector, d floats
-  const float* range_M;    // K floats
-  const float* range_m;    // K floats, or null: m = -M
-  uint8_t* packed;         // d*b/8 bytes
-  uint64_t d;
-  uint64_t j0;             // global coordinate of x[0] (a multiple of B): the random streams are indexed globally
-  TileMap tm;
-  uint32_t L;              // log2 B
-  uint32_t b, g;
-  uint32_t round, worker, k0, k1;
-  float c;                 // 1/sqrt(B)
-  uint32_t lut[256];       // per grid cell k: lo | wd << 8 | z0 << 16
-};
-
-struct QuantScalars {
-  float M, lo, sc16, c;  // range [lo, M]; for even log2 B they and sc16 are pre-scaled by c, and c is unused
-};
-
-template <bool CFOLD>
-__device__ __forceinline__ void quantize8(const float (&hv)[8], const uint4 rnd, const QuantScalars s,
-                                          const uint4* lut, uint32_t (&z)[8]) {
-  const uint32_t rw[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const float v = CFOLD ? hv[e] : hv[e] * s.c;
-    const float xc = __builtin_amdgcn_fmed3f(v, s.lo, s.M);
-    const float y16 = (xc - s.lo) * s.sc16;
-    const uint32_t ki = (uint32_t)y16;
-    const uint4 ent = lut[(ki >> 16) & 255u];
-    const float t16 = y16 - __uint_as_float(ent.x);
-    const float hf = (float)((e & 1) ? (rw[e >> 1] >> 16) : (rw[e >> 1] & 0xFFFFu));
-    const float prod = __builtin_fmaf(hf, __uint_as_float(ent.y), __uint_as_float(ent.z));
-    z[e] = ent.w + (prod < t16 ? 1u : 0u);
-  }
-}
-
-// eight B-bit fields, field 0 in the least significant bits
-template <int B>
-__device__ __forceinline__ uint32_t pack8(const uint32_t (&z)[8]) {
-  uint32_t w = z[7];
-#pragma unroll
-  for (int e = 6; e >= 0; --e) w = (w << B) | z[e];
-  return w;
-}
-
-__device__ __forceinline__ void store_packed8(uint8_t* packed, uint64_t j, uint32_t b, const uint32_t (&z)[8]) {
-  if (b == 4) {
-    *reinterpret_cast<uint32_t*>(packed + (j >> 1)) = pack8<4>(z);
-  } else if (b == 2) {
-    *reinterpret_cast<uint16_t*>(packed + (j >> 2)) = (uint16_t)pack8<2>(z);
-  } else if (b == 8) {
-    const uint32_t w0 = z[0] | z[1] << 8 | z[2] << 16 | z[3] << 24;
-    const uint32_t w1 = z[4] | z[5] << 8 | z[6] << 16 | z[7] << 24;
-    *reinterpret_cast<uint2*>(packed + j) = make_uint2(w0, w1);
-  } else if (b == 1) {
-    packed[j >> 3] = (uint8_t)pack8<1>(z);
-  } else {
-    store_fields8(packed + (j >> 3) * b, z, b);
-  }
-}
-
-// LDS entry of grid cell k: {lo * 2^16, wd, wd / 2 (all binary32, exact), z0}
-__device__ __forceinline__ uint4 quant_lut_entry(uint32_t ent) {
-  const float wd = (float)((ent >> 8) & 255u);
-  return make_uint4(__float_as_uint((float)(ent & 255u) * 65536.0f), __float_as_uint(wd), __float_as_uint(0.5f * wd),
-                    ent >> 16);
-}
-
-__device__ __forceinline__ void build_quant_lut(const QuantArgs& a, uint4* lut, int t) {
-  if (t < 256) lut[t] = quant_lut_entry(a.lut[t]);
-}
-
-// g / (M - m) * 2^16: the width in binary64, the quotient rounded once to binary32 (0 for an empty range)
-__device__ __forceinline__ float scale16_of(float M, float m, uint32_t g) {
-  const double W = (double)M - (double)m;
-  return W > 0.0 ? (float)((double)g / W) * 65536.0f : 0.f;
-}
-
-__device__ __forceinline__ float lower_of(const float* range_m, uint64_t blk, float M) {
-  return range_m ? range_m[blk] : -M;
-}
-
-template <int R, bool CFOLD>
-__global__ __launch_bounds__(NT, 8) void k_fwd_hi_quant(const QuantArgs a) {
-  __shared__ __align__(16) float lds[TILE];
-  __shared__ uint4 lut[256];
-  __shared__ float sM[8], sLo[8], sScale[8];
-
-  const int t = threadIdx.x;
-
-  if constexpr (R >= 2) {
-    const HiGeom<R> g(blockIdx.x, a.tm);
-    float4 x[4];
-    hi_issue_loads<R>(a.x, g, t, x);            // tile loads first: everything below overlaps their latency
-    build_quant_lut(a, lut, t);
-    if (t == 0) {                               // the whole tile lies in one block
-      const uint64_t blk = g.base >> a.L;
-      const float M = a.range_M[blk], m = lower_of(a.range_m, blk, M);
-      const float sc = scale16_of(M, m, a.g);
-      sM[0] = CFOLD ? M * (1.0f / a.c) : M;
-      sLo[0] = CFOLD ? m * (1.0f / a.c) : m;
-      sScale[0] = CFOLD ? sc * a.c : sc;
-    }
-    hi_r0_to_lds<R>(x, lds, t);
-    hi_round1<R>(lds, t);
-    int idx[2];
-    float v[2][8];
-    hi_back<R>(lds, t, idx, v);
-    const QuantScalars s{sM[0], sLo[0], sScale[0], a.c};
-    const uint64_t q0 = (a.j0 + g.base) >> 3;   // tiles start on multiples of 64 coordinates
-    uint8_t* const pk0 = a.packed + (g.base >> 3) * a.b;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const uint32_t o = g.off(idx[h]);
-      const uint64_t q = q0 + (o >> 3);
-      const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, a.worker, a.k0, a.k1);
-      uint32_t z[8];
-      quantize8<CFOLD>(v[h], rnd, s, lut, z);
-      store_packed8(pk0, o, a.b, z);
-    }
-  } else {
-    const HiGeom<R> g(blockIdx.x, a.tm);
-    build_quant_lut(a, lut, t);
-    // per-block scalars; a tile spans more than one block only when B < 8192 (then R == 0)
-    const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
-    if (t < nblk) {
-      const uint64_t blk = (g.base >> a.L) + t;
-      float M = 0.f, m = 0.f;
-      if (blk < (a.d >> a.L)) { M = a.range_M[blk]; m = lower_of(a.range_m, blk, M); }
-      sM[t] = M;
-      sLo[t] = m;
-      sScale[t] = scale16_of(M, m, a.g);
-    }
-    hi_load_to_lds<R>(a.x, g, a.d, lds, t);
-    lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, int, float) {});
-    __syncthreads();
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int idx = 8 * (t + NT * h);
-      const uint64_t j = g.coord(idx);
-      if (j >= a.d) continue;
-      const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
-      const QuantScalars s{sM[bt], sLo[bt], sScale[bt], a.c};
-      const float4 p0 = *reinterpret_cast<const float4*>(&lds[idx]);
-      const float4 p1 = *reinterpret_cast<const float4*>(&lds[idx + 4]);
-      const float hv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-      const uint64_t q = (a.j0 + j) >> 3;
-      const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, a.worker, a.k0, a.k1);
-      uint32_t z[8];
-      quantize8<false>(hv, rnd, s, lut, z);
-      store_packed8(a.packed, j, a.b, z);
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Sixteen consecutive codes (table indices or aggregated sums) of `bits` bits each, starting at
-// coordinate j (a multiple of 16): codes_load fetches the raw words (for the widths with a fast path)
-// or the decoded fields (any other width); codes_decode finishes the fast paths.
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void codes_load(const uint8_t* s8, uint32_t bits, uint64_t j, uint32_t (&w)[8],
-                                           uint32_t (&y)[16]) {
-  if (bits == 8) {
-    const uint4 r = *reinterpret_cast<const uint4*>(s8 + j);
-    w[0] = r.x; w[1] = r.y; w[2] = r.z; w[3] = r.w;
-  } else if (bits == 16) {
-    const uint4 r0 = *reinterpret_cast<const uint4*>(s8 + 2 * j);
-    const uint4 r1 = *reinterpret_cast<const uint4*>(s8 + 2 * j + 16);
-    w[0] = r0.x; w[1] = r0.y; w[2] = r0.z; w[3] = r0.w; w[4] = r1.x; w[5] = r1.y; w[6] = r1.z; w[7] = r1.w;
-  } else if (bits == 4) {
-    const uint2 r = *reinterpret_cast<const uint2*>(s8 + (j >> 1));
-    w[0] = r.x; w[1] = r.y;
-  } else if (bits == 2) {
-    w[0] = *reinterpret_cast<const uint32_t*>(s8 + (j >> 2));
-  } else if (bits == 1) {
-    w[0] = *reinterpret_cast<const uint16_t*>(s8 + (j >> 3));
-  } else {   // any other width: eight fields take `bits` bytes
-    uint32_t z0[8], z1[8];
-    load_fields8(s8 + (j >> 3) * bits, bits, z0);
-    load_fields8(s8 + ((j >> 3) + 1) * bits, bits, z1);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { y[e] = z0[e]; y[8 + e] = z1[e]; }
-  }
-}
-
-__device__ __forceinline__ void codes_decode(uint32_t bits, bool ok, const uint32_t (&w)[8], uint32_t (&y)[16]) {
-  if (bits == 8) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 2] >> (8 * (e & 3))) & 255u;
-  } else if (bits == 16) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-  } else if (bits == 4) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = (w[e >> 3] >> (4 * (e & 7))) & 15u;
-  } else if (bits == 2) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = (w[0] >> (2 * e)) & 3u;
-  } else if (bits == 1) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = (w[0] >> e) & 1u;
-  } else if (!ok) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) y[e] = 0;
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Inverse "lo" pass.  Source is either the aggregated stream (decompression, Alg. 2:
-// m + (Y/n)(M-m)/g = Y * step_n - M) or one worker's packed indices (error feedback, Alg. 3:
-// X_i = m + T[z](M-m)/g = T[z] * step_g - M).  One thread loads 16 consecutive coordinates.
-// ---------------------------------------------------------------------------------------------
-struct InvLoArgs {
-  const void* src;         // aggregated stream or packed indices
-  const float* range_M;
-  const float* range_m;    // or null: m = -M
-  float* ws_x;             // d floats, written
-  uint64_t d;
-  uint32_t L;
-  uint32_t src_bits;       // bits per coordinate in src
-  uint32_t use_table;      // 1: src holds table indices; 0: src holds aggregated table values
-  uint32_t divisor;        // g*n (aggregated) or g (indices)
-  TileMap tm;
-  uint8_t table[256];
-};
-
-template <int L1, bool XO>
-__global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
-  static_assert(!XO || L1 == LOG_TILE, "the row-split tile needs blocks of at least 2^16");
-  constexpr bool GUARD = L1 < LOG_TILE;
-  __shared__ __align__(16) float lds[TILE];
-  __shared__ float sM[8], sStep[8];
-  __shared__ float tabf[256];
-
-  const int t = threadIdx.x;
-  const uint64_t off = tm_base(a.tm, blockIdx.x);
-  const int idx = 16 * t;
-  const uint64_t j = off + lo_map<XO>(idx);
-  const bool ok = !GUARD || j < a.d;
-
-  // raw bits first, so the load is in flight while the block constants are prepared
-  uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  uint32_t y[16];
-  if (ok) codes_load(static_cast<const uint8_t*>(a.src), a.src_bits, j, w, y);
-
-  const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
-  if (t < nblk) {
-    const uint64_t blk = (off >> a.L) + t;
-    float M = 0.f, m = 0.f;
-    if (blk < (a.d >> a.L)) { M = a.range_M[blk]; m = lower_of(a.range_m, blk, M); }
-    sM[t] = m;                                                   // the affine map only needs the lower end
-    sStep[t] = (float)(((double)M - (double)m) / (double)a.divisor);
-  }
-  if (a.use_table && t < 256) tabf[t] = (float)a.table[t];
-  __syncthreads();
-
-  codes_decode(a.src_bits, ok, w, y);
-  const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
-  const float lo = sM[bt], step = sStep[bt];
-  float v[16];
-#pragma unroll
-  for (int e = 0; e < 16; ++e) {
-    const float f = a.use_table ? tabf[y[e]] : (float)y[e];
-    v[e] = ok ? f * step + lo : 0.f;
-  }
-  bfly<4>(v);
-#pragma unroll
-  for (int e = 0; e < 16; e += 4)
-    *reinterpret_cast<float4*>(&lds[swz(idx + e)]) = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
-
-  float* dst = a.ws_x + off;
-  const uint64_t left = a.d - off;
-  lds_stages<4, L1, true, SWZ>(lds, t, [&](int base, int eoff, float val) {
-    if (!GUARD || (uint64_t)(base + eoff) < left) dst[lo_map<XO>(base) + lo_map<XO>(eoff)] = val;
-  });
-}
-
-// ---------------------------------------------------------------------------------------------
-// Inverse "hi" pass: finish H, scale by 1/sqrt(B), apply the diagonal (Sec. 5.1: RHT^-1 = D H / sqrt(d)).
-// mode 0: out = result (Alg. 3, the global update);
-// mode 1: e <- (grad + e) - result (Alg. 3, error-feedback update), out = ef buffer, read and written.
-// ---------------------------------------------------------------------------------------------
-struct InvHiArgs {
-  const float* x;      // half-rotated vector, d floats
-  float* out;          // d floats
-  const void* grad;    // mode 1 only
-  uint64_t d;
-  uint64_t j0;         // global coordinate of x[0] (a multiple of B), for the diagonal's random stream
-  TileMap tm;
-  uint32_t round, k0, k1;
-  uint32_t mode, bf16;
-  float c;
-};
-
-__device__ __forceinline__ float4 inv_finish4(float4 v, uint32_t bits, const InvHiArgs& a, uint64_t j) {
-  v.x = flip(v.x * a.c, bits & 1u);
-  v.y = flip(v.y * a.c, (bits >> 1) & 1u);
-  v.z = flip(v.z * a.c, (bits >> 2) & 1u);
-  v.w = flip(v.w * a.c, (bits >> 3) & 1u);
-  if (a.mode == 1) {
-    float4 x = a.bf16 ? load_grad4<true>(a.grad, j) : load_grad4<false>(a.grad, j);
-    const float4 e = *reinterpret_cast<const float4*>(a.out + j);
-    x.x += e.x; x.y += e.y; x.z += e.z; x.w += e.w;
-    v = make_float4(x.x - v.x, x.y - v.y, x.z - v.z, x.w - v.w);
-  }
-  return v;
-}
-
-template <int R>
-__global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
-  __shared__ __align__(16) float lds[TILE];
-  __shared__ uint32_t sgn[TILE / 32];
-
-  const int t = threadIdx.x;
-  const HiGeom<R> g(blockIdx.x, a.tm);
-
-  if constexpr (R >= 2) {
-    hi_front<R>(a.x, g, lds, t);
-    // 32 consecutive tile indices are 32 consecutive coordinates (rows are at least 64 wide)
-    if (t < TILE / 32) sgn[t] = sign_word(a.j0 + g.coord(32 * t), a.round, a.k0, a.k1);
-    int idx[2];
-    float v[2][8];
-    hi_back<R>(lds, t, idx, v);
-    __syncthreads();
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const uint64_t j = g.coord(idx[h]);
-      const uint32_t bits = sgn[idx[h] >> 5] >> (idx[h] & 31);
-      const float4 o0 = inv_finish4(make_float4(v[h][0], v[h][1], v[h][2], v[h][3]), bits, a, j);
-      const float4 o1 = inv_finish4(make_float4(v[h][4], v[h][5], v[h][6], v[h][7]), bits >> 4, a, j + 4);
-      *reinterpret_cast<float4*>(a.out + j) = o0;
-      *reinterpret_cast<float4*>(a.out + j + 4) = o1;
-    }
-  } else {
-    if (t < TILE / 32) sgn[t] = sign_word(a.j0 + g.coord(32 * t), a.round, a.k0, a.k1);
-    hi_load_to_lds<R>(a.x, g, a.d, lds, t);
-    lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, int, float) {});
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int idx = 4 * (i * NT + t);
-      const uint64_t j = g.coord(idx);
-      if (j >= a.d) continue;
-      const float4 v = *reinterpret_cast<const float4*>(&lds[idx]);
-      const uint32_t bits = sgn[idx >> 5] >> (idx & 31);
-      *reinterpret_cast<float4*>(a.out + j) = inv_finish4(v, bits, a, j);
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Uniform THC (Alg. 1).  Preliminary stage: every worker's minimum and maximum per block, then the
-// global ones.  Main stage: uniform stochastic quantization = the same quantizer with the identity
-// table, on the gradients themselves or (ablation of App. C) on their RHT.
-// Partial minima / maxima: one per min(B, 8192) coordinates per worker, like the partial sums of squares.
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float wave_min(float v) {
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1) v = __builtin_fminf(v, __shfl_xor(v, m, 64));
-  return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1) v = __builtin_fmaxf(v, __shfl_xor(v, m, 64));
-  return v;
-}
-
-struct MinMaxArgs {
-  PtrArr grads;
-  PtrArr efs;
-  float* pmin;       // n * (d >> L1)
-  float* pmax;
-  uint64_t d;
-  uint32_t L1;       // log2 of min(B, 8192)
-};
-
-template <bool BF16, bool EF>
-__global__ __launch_bounds__(NT) void k_minmax(const MinMaxArgs a) {
-  __shared__ float smin[32], smax[32];   // one per 256 consecutive coordinates of the tile
-  const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
-  const uint32_t worker = blockIdx.y;
-  const uint64_t off = (uint64_t)blockIdx.x << LOG_TILE;
-  const float* ef = EF ? static_cast<const float*>(a.efs.p[worker]) : nullptr;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint64_t j = off + 4u * (uint32_t)(i * NT + t);
-    float mn = __builtin_inff(), mx = -__builtin_inff();
-    if (j < a.d) {
-      float4 x = load_grad4<BF16>(a.grads.p[worker], j);
-      if constexpr (EF) {
-        const float4 e = *reinterpret_cast<const float4*>(ef + j);
-        x.x += e.x; x.y += e.y; x.z += e.z; x.w += e.w;
-      }
-      mn = __builtin_fminf(__builtin_fminf(x.x, x.y), __builtin_fminf(x.z, x.w));
-      mx = __builtin_fmaxf(__builtin_fmaxf(x.x, x.y), __builtin_fmaxf(x.z, x.w));
-    }
-    mn = wave_min(mn);
-    mx = wave_max(mx);
-    if (lane == 0) { smin[i * 8 + wave] = mn; smax[i * 8 + wave] = mx; }
-  }
-  __syncthreads();
-  const int nblk = TILE >> a.L1, cpb = 32 / nblk;   // chunks of 256 per block inside the tile
-  if (t < nblk) {
-    float mn = __builtin_inff(), mx = -__builtin_inff();
-    for (int c = 0; c < cpb; ++c) {
-      mn = __builtin_fminf(mn, smin[t * cpb + c]);
-      mx = __builtin_fmaxf(mx, smax[t * cpb + c]);
-    }
-    const uint64_t pidx = (off >> a.L1) + t;
-    if (pidx < (a.d >> a.L1)) {
-      a.pmin[(uint64_t)worker * (a.d >> a.L1) + pidx] = mn;
-      a.pmax[(uint64_t)worker * (a.d >> a.L1) + pidx] = mx;
-    }
-  }
-}
-
-struct MinMaxFinalArgs {
-  const float* pmin;
-  const float* pmax;
-  float* range_m;
-  float* range_M;
-  uint64_t d;
-  uint32_t n, L, L1;
-};
-
-__global__ __launch_bounds__(64) void k_minmax_final(const MinMaxFinalArgs a) {
-  const uint64_t k = blockIdx.x;
-  const int lane = threadIdx.x;
-  const uint32_t ppb = 1u << (a.L - a.L1);
-  const uint64_t per_worker = a.d >> a.L1;
-  float mn = __builtin_inff(), mx = -__builtin_inff();
-  for (uint32_t i = 0; i < a.n; ++i) {
-    const uint64_t base = (uint64_t)i * per_worker + k * ppb;
-    for (uint32_t j = lane; j < ppb; j += 64) {
-      mn = __builtin_fminf(mn, a.pmin[base + j]);
-      mx = __builtin_fmaxf(mx, a.pmax[base + j]);
-    }
-  }
-  mn = wave_min(mn);
-  mx = wave_max(mx);
-  if (lane == 0) { a.range_m[k] = mn; a.range_M[k] = mx; }
-}
-
-// Last strided pass of a forward RHT that keeps the rotated vector: finishes the butterflies, scales by
-// 1/sqrt(B), writes the result back in place and records the tile's minimum and maximum.
-struct HiStoreArgs {
-  float* x;          // one worker's half-rotated vector, d floats, rotated in place
-  float* pmin;       // this worker's partial minima, d >> L1 floats
-  float* pmax;
-  uint64_t d;
-  TileMap tm;
-  uint32_t L;
-  float c;
-};
-
-template <int R>
-__global__ __launch_bounds__(NT) void k_fwd_hi_store(const HiStoreArgs a) {
-  __shared__ __align__(16) float lds[TILE];
-  __shared__ float smin[16], smax[16];
-  const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
-  const HiGeom<R> g(blockIdx.x, a.tm);
-  if constexpr (R >= 2) {
-    hi_front<R>(a.x, g, lds, t);
-    int idx[2];
-    float v[2][8];
-    hi_back<R>(lds, t, idx, v);
-    float mn = __builtin_inff(), mx = -__builtin_inff();
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        v[h][e] *= a.c;
-        mn = __builtin_fminf(mn, v[h][e]);
-        mx = __builtin_fmaxf(mx, v[h][e]);
-      }
-      float* o = a.x + g.coord(idx[h]);
-      *reinterpret_cast<float4*>(o) = make_float4(v[h][0], v[h][1], v[h][2], v[h][3]);
-      *reinterpret_cast<float4*>(o + 4) = make_float4(v[h][4], v[h][5], v[h][6], v[h][7]);
-    }
-    mn = wave_min(mn);
-    mx = wave_max(mx);
-    if (lane == 0) { smin[wave] = mn; smax[wave] = mx; }
-    __syncthreads();
-    if (t == 0) {   // the whole tile lies in one block: one partial per tile
-      for (int w = 1; w < 8; ++w) { mn = __builtin_fminf(mn, smin[w]); mx = __builtin_fmaxf(mx, smax[w]); }
-      a.pmin[blockIdx.x] = mn;
-      a.pmax[blockIdx.x] = mx;
-    }
-  } else {
-    hi_load_to_lds<R>(a.x, g, a.d, lds, t);
-    lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, int, float) {});
-    __syncthreads();
-    // thread owns tile indices [8(t + 512h), +8): a wave covers 512 consecutive values per h
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int idx = 8 * (t + NT * h);
-      const uint64_t j = g.coord(idx);
-      float mn = __builtin_inff(), mx = -__builtin_inff();
-      if (j < a.d) {
-        float4 p0 = *reinterpret_cast<const float4*>(&lds[idx]);
-        float4 p1 = *reinterpret_cast<const float4*>(&lds[idx + 4]);
-        p0.x *= a.c; p0.y *= a.c; p0.z *= a.c; p0.w *= a.c;
-        p1.x *= a.c; p1.y *= a.c; p1.z *= a.c; p1.w *= a.c;
-        *reinterpret_cast<float4*>(a.x + j) = p0;
-        *reinterpret_cast<float4*>(a.x + j + 4) = p1;
-        mn = __builtin_fminf(__builtin_fminf(__builtin_fminf(p0.x, p0.y), __builtin_fminf(p0.z, p0.w)),
-                             __builtin_fminf(__builtin_fminf(p1.x, p1.y), __builtin_fminf(p1.z, p1.w)));
-        mx = __builtin_fmaxf(__builtin_fmaxf(__builtin_fmaxf(p0.x, p0.y), __builtin_fmaxf(p0.z, p0.w)),
-                             __builtin_fmaxf(__builtin_fmaxf(p1.x, p1.y), __builtin_fmaxf(p1.z, p1.w)));
-      }
-      mn = wave_min(mn);
-      mx = wave_max(mx);
-      if (lane == 0) { smin[h * 8 + wave] = mn; smax[h * 8 + wave] = mx; }
-    }
-    __syncthreads();
-    // blocks inside the tile (B < 8192) or the single one (then R rows of one block share the tile)
-    const uint32_t L1 = a.L < LOG_TILE ? a.L : LOG_TILE;
-    const int nblk = TILE >> L1, cpb = 16 / nblk;    // chunks of 512 per block inside the tile
-    if (t < nblk) {
-      float mn = __builtin_inff(), mx = -__builtin_inff();
-      for (int c = 0; c < cpb; ++c) {
-        mn = __builtin_fminf(mn, smin[t * cpb + c]);
-        mx = __builtin_fmaxf(mx, smax[t * cpb + c]);
-      }
-      const uint64_t pidx = ((uint64_t)blockIdx.x << (LOG_TILE - L1)) + t;
-      if (pidx < (a.d >> L1)) { a.pmin[pidx] = mn; a.pmax[pidx] = mx; }
-    }
-  }
-}
-
-// Uniform stochastic quantization of one worker's vector: 8192 consecutive coordinates per workgroup.
-// Source: the rotated vector `x` when given, else grad (+ e).  Without rotation the error-feedback update
-// e <- x - (m + z (M-m)/g) is done here; with rotation it needs an inverse transform (separate passes).
-struct UQuantArgs {
-  const float* x;          // rotated vector or null
-  const void* grad;
-  float* ef;               // error feedback, read (and written when ef_update) or null
-  const float* range_M;
-  const float* range_m;
-  uint8_t* packed;
-  uint64_t d;
-  uint32_t L, b, g;
-  uint32_t round, worker, k0, k1;
-  uint32_t ef_update;
-  uint64_t j0;             // global coordinate of the first element
-  uint32_t lut[256];
-};
-
-template <bool BF16>
-__global__ __launch_bounds__(NT) void k_uniform_quant(const UQuantArgs a) {
-  __shared__ uint4 lut[256];
-  __shared__ float sM[8], sLo[8], sScale[8], sStep[8];
-  const int t = threadIdx.x;
-  const uint64_t off = (uint64_t)blockIdx.x << LOG_TILE;
-  if (t < 256) {
-    lut[t] = quant_lut_entry(a.lut[t]);
-  }
-  const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
-  if (t < nblk) {
-    const uint64_t blk = (off >> a.L) + t;
-    float M = 0.f, m = 0.f;
-    if (blk < (a.d >> a.L)) { M = a.range_M[blk]; m = lower_of(a.range_m, blk, M); }
-    sM[t] = M;
-    sLo[t] = m;
-    sScale[t] = scale16_of(M, m, a.g);
-    sStep[t] = (float)(((double)M - (double)m) / (double)a.g);
-  }
-  __syncthreads();
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int idx = 8 * (t + NT * h);
-    const uint64_t j = off + idx;
-    if (j >= a.d) continue;
-    float4 p0, p1;
-    if (a.x) {
-      p0 = *reinterpret_cast<const float4*>(a.x + j);
-      p1 = *reinterpret_cast<const float4*>(a.x + j + 4);
-    } else {
-      p0 = load_grad4<BF16>(a.grad, j);
-      p1 = load_grad4<BF16>(a.grad, j + 4);
-      if (a.ef) {
-        const float4 e0 = *reinterpret_cast<const float4*>(a.ef + j);
-        const float4 e1 = *reinterpret_cast<const float4*>(a.ef + j + 4);
-        p0.x += e0.x; p0.y += e0.y; p0.z += e0.z; p0.w += e0.w;
-        p1.x += e1.x; p1.y += e1.y; p1.z += e1.z; p1.w += e1.w;
-      }
-    }
-    const float hv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-    const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
-    const QuantScalars s{sM[bt], sLo[bt], sScale[bt], 1.0f};
-    const uint64_t q = (a.j0 + j) >> 3;
-    const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, a.worker, a.k0, a.k1);
-    uint32_t z[8];
-    quantize8<true>(hv, rnd, s, lut, z);          // no scaling: the values are final
-    store_packed8(a.packed, j, a.b, z);
-    if (a.ef_update) {
-      const float step = sStep[bt], lo = sLo[bt];
-      float e[8];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) e[k] = hv[k] - ((float)z[k] * step + lo);   // identity table: T[z] = z
-      *reinterpret_cast<float4*>(a.ef + j) = make_float4(e[0], e[1], e[2], e[3]);
-      *reinterpret_cast<float4*>(a.ef + j + 4) = make_float4(e[4], e[5], e[6], e[7]);
-    }
-  }
-}
-
-// Alg. 1's estimate without rotation: out = m + X (M-m)/(g n), sixteen coordinates per thread.
-struct UDequantArgs {
-  const void* agg;
-  const float* range_M;
-  const float* range_m;
-  float* out;
-  uint64_t d;
-  uint32_t L, agg_bits, divisor;
-};
-
-__global__ __launch_bounds__(256) void k_uniform_dequant(const UDequantArgs a) {
-  const uint64_t j = ((uint64_t)blockIdx.x * 256 + threadIdx.x) * 16;
-  if (j >= a.d) return;
-  uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0}, y[16];
-  codes_load(static_cast<const uint8_t*>(a.agg), a.agg_bits, j, w, y);
-  codes_decode(a.agg_bits, true, w, y);
-  const uint64_t blk = j >> a.L;
-  const float M = a.range_M[blk], m = lower_of(a.range_m, blk, M);
-  const float step = (float)(((double)M - (double)m) / (double)a.divisor);
-  float v[16];
-#pragma unroll
-  for (int e = 0; e < 16; ++e) v[e] = (float)y[e] * step + m;
-#pragma unroll
-  for (int e = 0; e < 16; e += 4)
-    *reinterpret_cast<float4*>(a.out + j + e) = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Aggregation (Alg. 2: Y = sum_i T[Z_i]; the PS only looks up and adds).  Generic path: one thread
-// owns 16 consecutive coordinates of every stream; table in LDS.
-// ---------------------------------------------------------------------------------------------
-struct AggArgs {
-  PtrArr packed;
-  void* out;
-  uint64_t d;
-  uint32_t n, b, agg_bits;
-  uint8_t table[256];
-};
-
-__global__ __launch_bounds__(256) void k_aggregate_generic(const AggArgs a) {
-  __shared__ uint32_t tab[256];
-  tab[threadIdx.x] = a.table[threadIdx.x];
-  __syncthreads();
-  const uint64_t j = ((uint64_t)blockIdx.x * 256 + threadIdx.x) * 16;
-  if (j >= a.d) return;
-  uint32_t acc[16];
-#pragma unroll
-  for (int e = 0; e < 16; ++e) acc[e] = 0;
-  for (uint32_t i = 0; i < a.n; ++i) {
-    const uint8_t* s8 = static_cast<const uint8_t*>(a.packed.p[i]);
-    if (a.b == 4) {
-      const uint2 r = *reinterpret_cast<const uint2*>(s8 + (j >> 1));
-      const uint32_t w[2] = {r.x, r.y};
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[e] += tab[(w[e >> 3] >> (4 * (e & 7))) & 15u];
-    } else if (a.b == 2) {
-      const uint32_t w = *reinterpret_cast<const uint32_t*>(s8 + (j >> 2));
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[e] += tab[(w >> (2 * e)) & 3u];
-    } else if (a.b == 8) {
-      const uint4 r = *reinterpret_cast<const uint4*>(s8 + j);
-      const uint32_t w[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[e] += tab[(w[e >> 2] >> (8 * (e & 3))) & 255u];
-    } else if (a.b == 1) {
-      const uint32_t w = *reinterpret_cast<const uint16_t*>(s8 + (j >> 3));
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[e] += tab[(w >> e) & 1u];
-    } else {
-      uint32_t z0[8], z1[8];
-      load_fields8(s8 + (j >> 3) * a.b, a.b, z0);
-      load_fields8(s8 + ((j >> 3) + 1) * a.b, a.b, z1);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { acc[e] += tab[z0[e]]; acc[8 + e] += tab[z1[e]]; }
-    }
-  }
-  uint8_t* out = static_cast<uint8_t*>(a.out);
-  if (a.agg_bits == 8) {
-    uint32_t w[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) w[k] = acc[4 * k] | acc[4 * k + 1] << 8 | acc[4 * k + 2] << 16 | acc[4 * k + 3] << 24;
-    *reinterpret_cast<uint4*>(out + j) = make_uint4(w[0], w[1], w[2], w[3]);
-  } else if (a.agg_bits == 16) {
-    uint32_t w[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) w[k] = acc[2 * k] | acc[2 * k + 1] << 16;
-    uint4* o = reinterpret_cast<uint4*>(out + 2 * j);
-    o[0] = make_uint4(w[0], w[1], w[2], w[3]);
-    o[1] = make_uint4(w[4], w[5], w[6], w[7]);
-  } else {   // exact-width sums (Sec. 8.4: ceil(log2(g n + 1)) bits are enough)
-    uint32_t z0[8], z1[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { z0[e] = acc[e]; z1[e] = acc[8 + e]; }
-    store_fields8(out + (j >> 3) * a.agg_bits, z0, a.agg_bits);
-    store_fields8(out + ((j >> 3) + 1) * a.agg_bits, z1, a.agg_bits);
-  }
-}
-
-// 4-bit indices -> 8-bit sums, the paper's prototype widths (Sec. 3).  One thread owns 32 coordinates
-// (16 bytes of every stream); the 16-entry table sits in four registers and is applied to four
-// nibbles at a time with byte permutes; sums of four coordinates share a register (no carry can
-// cross a byte because g*n <= 255).
-struct AggB4Args {
-  PtrArr packed;
-  uint8_t* out;
-  uint64_t nvec;    // d / 32
-  uint32_t n;
-  uint32_t tb[4];   // table bytes 0..15, little endian
-};
-
-__device__ __forceinline__ uint32_t lut16x4(uint32_t sel, const uint32_t (&tb)[4]) {
-  const uint32_t s7 = sel & 0x07070707u;
-  const uint32_t lo = __builtin_amdgcn_perm(tb[1], tb[0], s7);
-  const uint32_t hi = __builtin_amdgcn_perm(tb[3], tb[2], s7);
-  const uint32_t m = ((sel & 0x08080808u) >> 3) * 0xFFu;
-  return (hi & m) | (lo & ~m);
-}
-
-__global__ __launch_bounds__(256) void k_aggregate_b4w8(const AggB4Args a) {
-  const uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-  if (v >= a.nvec) return;
-  const uint32_t tb[4] = {a.tb[0], a.tb[1], a.tb[2], a.tb[3]};
-  uint32_t ev[4] = {0, 0, 0, 0}, od[4] = {0, 0, 0, 0};
-  for (uint32_t i = 0; i < a.n; ++i) {
-    const uint4 r = reinterpret_cast<const uint4*>(a.packed.p[i])[v];
-    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      ev[k] += lut16x4(w[k] & 0x0F0F0F0Fu, tb);          // coordinates 8k + 0, 2, 4, 6
-      od[k] += lut16x4((w[k] >> 4) & 0x0F0F0F0Fu, tb);   // coordinates 8k + 1, 3, 5, 7
-    }
-  }
-  uint32_t o[8];
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    o[2 * k] = __builtin_amdgcn_perm(od[k], ev[k], 0x05010400u);
-    o[2 * k + 1] = __builtin_amdgcn_perm(od[k], ev[k], 0x07030602u);
-  }
-  uint4* dst = reinterpret_cast<uint4*>(a.out + v * 32);
-  dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
-  dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
-}
-
-// 4-bit indices -> 16-bit sums (g*n above 255).  Same lookups; workers are taken in runs of `chunk` =
-// floor(255 / g), inside which the byte-wise sums cannot carry, and every run is then widened into 16-bit lanes.
-struct AggB4W16Args {
-  PtrArr packed;
-  uint8_t* out;
-  uint64_t nvec;    // d / 32
-  uint32_t n, chunk;
-  uint32_t tb[4];
-};
-
-__global__ __launch_bounds__(256) void k_aggregate_b4w16(const AggB4W16Args a) {
-  const uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-  if (v >= a.nvec) return;
-  const uint32_t tb[4] = {a.tb[0], a.tb[1], a.tb[2], a.tb[3]};
-  uint32_t acc[16];   // acc[4k + m] = sums of coordinates 8k + 2m (low half) and 8k + 2m + 1 (high half)
-#pragma unroll
-  for (int e = 0; e < 16; ++e) acc[e] = 0;
-  for (uint32_t i0 = 0; i0 < a.n; i0 += a.chunk) {
-    const uint32_t i1 = (i0 + a.chunk < a.n) ? i0 + a.chunk : a.n;
-    uint32_t ev[4] = {0, 0, 0, 0}, od[4] = {0, 0, 0, 0};
-    for (uint32_t i = i0; i < i1; ++i) {
-      const uint4 r = reinterpret_cast<const uint4*>(a.packed.p[i])[v];
-      const uint32_t w[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        ev[k] += lut16x4(w[k] & 0x0F0F0F0Fu, tb);
-        od[k] += lut16x4((w[k] >> 4) & 0x0F0F0F0Fu, tb);
-      }
-    }
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      acc[4 * k + 0] += __builtin_amdgcn_perm(od[k], ev[k], 0x0C040C00u);
-      acc[4 * k + 1] += __builtin_amdgcn_perm(od[k], ev[k], 0x0C050C01u);
-      acc[4 * k + 2] += __builtin_amdgcn_perm(od[k], ev[k], 0x0C060C02u);
-      acc[4 * k + 3] += __builtin_amdgcn_perm(od[k], ev[k], 0x0C070C03u);
-    }
-  }
-  uint4* dst = reinterpret_cast<uint4*>(a.out + v * 64);
-#pragma unroll
-  for (int k = 0; k < 4; ++k) dst[k] = make_uint4(acc[4 * k], acc[4 * k + 1], acc[4 * k + 2], acc[4 * k + 3]);
-}
-
-// 2-bit indices -> 8-bit sums.  One thread owns 64 coordinates (16 bytes of every stream); the four table
-// values sit in one register; field f of every byte is looked up with one byte permute, so acc[k][f] holds the
-// sums of coordinates 16k + 4*byte + f, and a 4x4 byte transpose restores coordinate order at the end.
-struct AggB2Args {
-  PtrArr packed;
-  uint8_t* out;
-  uint64_t nvec;    // d / 64
-  uint32_t n;
-  uint32_t tb;      // table bytes 0..3, little endian
-};
-
-__global__ __launch_bounds__(256) void k_aggregate_b2w8(const AggB2Args a) {
-  const uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-  if (v >= a.nvec) return;
-  uint32_t acc[4][4];
-#pragma unroll
-  for (int k = 0; k < 4; ++k)
-#pragma unroll
-    for (int f = 0; f < 4; ++f) acc[k][f] = 0;
-  for (uint32_t i = 0; i < a.n; ++i) {
-    const uint4 r = reinterpret_cast<const uint4*>(a.packed.p[i])[v];
-    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-#pragma unroll
-      for (int f = 0; f < 4; ++f) acc[k][f] += __builtin_amdgcn_perm(0u, a.tb, (w[k] >> (2 * f)) & 0x03030303u);
-  }
-  uint4* dst = reinterpret_cast<uint4*>(a.out + v * 64);
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const uint32_t p0 = __builtin_amdgcn_perm(acc[k][1], acc[k][0], 0x05010400u);   // bytes 0, 1 of fields 0, 1
-    const uint32_t p1 = __builtin_amdgcn_perm(acc[k][1], acc[k][0], 0x07030602u);   // bytes 2, 3
-    const uint32_t q0 = __builtin_amdgcn_perm(acc[k][3], acc[k][2], 0x05010400u);
-    const uint32_t q1 = __builtin_amdgcn_perm(acc[k][3], acc[k][2], 0x07030602u);
-    dst[k] = make_uint4(__builtin_amdgcn_perm(q0, p0, 0x05040100u), __builtin_amdgcn_perm(q0, p0, 0x07060302u),
-                        __builtin_amdgcn_perm(q1, p1, 0x05040100u), __builtin_amdgcn_perm(q1, p1, 0x07060302u));
-  }
-}
-
-}  // namespace thc
+#include "thc_forward.hpp"
+#include "thc_inverse.hpp"
+#include "thc_uniform.hpp"
+#include "thc_aggregate.hpp"
