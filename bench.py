@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--variant", choices=("thc", "uniform", "uniform-rotated"), default="thc",
                     help="thc: Alg. 3 (the headline).  uniform / uniform-rotated: Alg. 1 on the same workload "
                          "(identity table, g = 2^b - 1, min/max ranges), without / with the rotation")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one round in a HIP graph and replay it (the round counter then stays fixed): for "
+                         "small vectors, where the dozen launches of a round dominate")
     ap.add_argument("--agg-bits", type=int, default=0, help="override the width of the aggregated sums (1..16)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device-to-device copy five times and exit (reference for HBM byte counters)")
@@ -143,11 +146,31 @@ def main():
     for r in range(args.warmup):
         step(r, False)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for r in range(args.steps):
-        step(args.warmup + r, True)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    if args.graph:
+        cap = torch.cuda.Stream()
+        cap.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(cap):
+            step(args.warmup, False)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=cap):
+                step(args.warmup, False)
+        torch.cuda.current_stream().wait_stream(cap)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for r in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        step(args.warmup, True)                 # one eager round for the per-stage split
+        torch.cuda.synchronize()
+    else:
+        t0 = time.perf_counter()
+        for r in range(args.steps):
+            step(args.warmup + r, True)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
 
     ms_per_step = dt / args.steps * 1e3
     stage_ms = {name: sum(ev[k].elapsed_time(ev[k + 1]) for ev in events) / len(events)
@@ -174,7 +197,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "d_padded": w.d, "d_real": w.real, "rht_block": w.block, "workers": w.n,
                    "b": w.b, "g": w.g, "agg_bits": w.agg_bits, "error_feedback": w.ef, "input": w.dtype,
-                   "stage_order": args.stage_order, "variant": args.variant},
+                   "stage_order": args.stage_order, "variant": args.variant, "hip_graph": args.graph},
         "worker_coords_per_s": w.n * w.d / (dt / args.steps),
         "effective_hbm_GBps": bpc * w.d / (dt / args.steps) / 1e9,
         "effective_hbm_frac": bpc * w.d / (dt / args.steps) / 1e9 / HBM_PEAK_GBPS,

@@ -125,7 +125,8 @@ int thc_compress(const thc_params* p, uint32_t worker_id, uint64_t round, const 
 /* Main stage, PS side (Alg. 2: Y = sum_i T[Z_i]; the PS pseudocode's lookup + aggregate steps).
  *   packed    host array of n device pointers, each d*b/8 bytes.
  *   agg_out   device, d * agg_bits/8 bytes, written.
- * Aggregating a subset of workers (partial aggregation, Sec. 6) is a call with a smaller p->n. */
+ * Aggregating a subset of workers (partial aggregation, Sec. 6) is a call with that subset's pointers and count
+ * in p->n; thc_decompress then takes the same p->n (it divides by the number of workers that were added up). */
 int thc_aggregate(const thc_params* p, const uint8_t* const* packed /* host */, void* agg_out, void* stream);
 
 /* Worker side after the PS (Alg. 2 / Alg. 3: Y_avg = Y/n; x' = m + Y_avg (M-m)/g; RHT^-1).
