@@ -143,7 +143,7 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Range (Sec. 5.3; Alg. 3: M = (t_p / sqrt(d)) * max_i ||x_i||, per block).  One wave per block.
+// Range (Sec. 5.3; Alg. 3: M = (t_p / sqrt(d)) * max_i ||x_i||, per block).
 // ---------------------------------------------------------------------------------------------
 struct RangeArgs {
   const double* partials;   // n * (d >> L1)
