@@ -272,6 +272,29 @@ struct UDequantArgs {
 };
 
 __global__ __launch_bounds__(256) void k_uniform_dequant(const UDequantArgs a) {
+  if (a.agg_bits == 8 || a.agg_bits == 16) {
+    // byte-aligned sums: four coordinates per thread and step, so that a wave writes 1 KB at a time
+    const uint64_t base = (uint64_t)blockIdx.x * 4096;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint64_t j = base + 1024u * k + 4u * threadIdx.x;
+      if (j >= a.d) return;
+      uint32_t y[4];
+      if (a.agg_bits == 8) {
+        const uint32_t c = *reinterpret_cast<const uint32_t*>(static_cast<const uint8_t*>(a.agg) + j);
+        y[0] = c & 255u; y[1] = (c >> 8) & 255u; y[2] = (c >> 16) & 255u; y[3] = c >> 24;
+      } else {
+        const uint2 c = *reinterpret_cast<const uint2*>(static_cast<const uint8_t*>(a.agg) + 2 * j);
+        y[0] = c.x & 0xFFFFu; y[1] = c.x >> 16; y[2] = c.y & 0xFFFFu; y[3] = c.y >> 16;
+      }
+      const uint64_t blk = j >> a.L;
+      const float M = a.range_M[blk], m = lower_of(a.range_m, blk, M);
+      const float step = (float)(((double)M - (double)m) / (double)a.divisor);
+      *reinterpret_cast<float4*>(a.out + j) =
+          make_float4((float)y[0] * step + m, (float)y[1] * step + m, (float)y[2] * step + m, (float)y[3] * step + m);
+    }
+    return;
+  }
   const uint64_t j = ((uint64_t)blockIdx.x * 256 + threadIdx.x) * 16;
   if (j >= a.d) return;
   uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0}, y[16];
