@@ -21,8 +21,10 @@
  *   - The library allocates nothing and keeps no state: workspace, range, error-feedback buffers, the
  *     round counter and the lookup table are owned by the caller.  Inputs are never modified, except
  *     `ef_inout`.
- *   - Return value: THC_OK (0) or a negative thc_status.  Non-finite inputs are not detected; they
- *     propagate to unspecified (but in-bounds) results.
+ *   - Return value: THC_OK (0) or a negative thc_status.  Non-finite inputs (or inputs so large that their
+ *     transform overflows binary32) are not detected; they propagate to unspecified (but in-bounds) results.
+ *     A block whose range width M - m is below 2^-100 counts as empty: all its indices are 0 and it decodes
+ *     to m (this covers the all-zero block, M = 0, which decodes to exact zeros).
  *   - Vector layout: a worker's gradient is one flat vector of d coordinates (padded by the caller with
  *     zeros to a multiple of `block`).  The RHT, the norm and the range are per block of `block`
  *     consecutive coordinates (the paper's 4 MB partition is block = 2^20).

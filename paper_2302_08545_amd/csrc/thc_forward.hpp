@@ -421,10 +421,12 @@ __device__ __forceinline__ void build_quant_lut(const QuantArgs& a, uint4* lut, 
   if (t < 256) lut[t] = quant_lut_entry(a.lut[t]);
 }
 
-// g / (M - m) * 2^16: the width in binary64, the quotient rounded once to binary32 (0 for an empty range)
+// g / (M - m) * 2^16: the width in binary64, the quotient rounded once to binary32.  An empty range gives 0 (every
+// index 0); widths below 2^-100 count as empty: there the scale, its 2^16 multiple and the folded 1/sqrt(B) would
+// leave binary32's normal range.
 __device__ __forceinline__ float scale16_of(float M, float m, uint32_t g) {
   const double W = (double)M - (double)m;
-  return W > 0.0 ? (float)((double)g / W) * 65536.0f : 0.f;
+  return W >= 0x1p-100 ? (float)((double)g / W) * 65536.0f : 0.f;
 }
 
 __device__ __forceinline__ float lower_of(const float* range_m, uint64_t blk, float M) {

@@ -569,6 +569,37 @@ def test_all_zero_block_and_zero_padding():
         assert rel_l2(got, out) <= 1e-5
 
 
+@pytest.mark.parametrize("L,order", [(12, 0), (13, 0), (16, 1), (17, 1)])
+@pytest.mark.parametrize("k", [-80, 40, -92, -93, -120])
+def test_very_small_and_very_large_magnitudes(L, order, k):
+    """Inputs scaled by 2^k: the indices must equal the oracle's at every magnitude (binary32 has the exponent range,
+    and the kernels' 2^16-scaled grid and folded 1/sqrt(B) must not leave it); ranges narrower than 2^-100 count as
+    empty on both sides.  M is about 2.8e-3 * 2^k here, so k = -92 is the last magnitude above the cutoff and
+    k = -93 the first below it."""
+    block, K, n = 1 << L, 2, 2
+    d = block * K
+    P, Lp = both_params(d, block, n, order=order)
+    grads = [g * (2.0 ** k) for g in make_grads(d, n, seed=L)]
+    dg = [x.to(DEV) for x in grads]
+    gn = [to_np32(x) for x in grads]
+    R = GpuRound(Lp)
+    R.prepare(1, dg)
+    M_ref = o.prepare_range(P, gn)
+    assert np.all(np.abs(R.range_M.cpu().numpy() - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
+    Md = torch.from_numpy(M_ref).to(DEV)
+    R.compress_all(1, dg, range_M=Md)
+    pks = [o.compress(P, i, 1, gn[i], None, M_ref)[0] for i in range(n)]
+    for i in range(n):
+        assert np.array_equal(R.packed[i].cpu().numpy(), pks[i]), f"worker {i}"
+    if k <= -93:
+        assert all(not pk.any() for pk in pks)
+    else:
+        assert all(pk.any() for pk in pks)
+    R.aggregate()
+    R.decompress(1, range_M=Md)
+    assert rel_l2(R.out.cpu().numpy(), o.decompress(P, 1, o.aggregate(P, pks), M_ref)) <= 1e-5
+
+
 def test_truncation_is_taken_like_the_oracle():
     """Rotated coordinates beyond +-M are truncated (Alg. 3): for the worker with the largest norm about a
     p/2 fraction lands on the first and on the last index; an explicitly narrow range clamps far more."""
