@@ -73,7 +73,7 @@ enum { THC_ORDER_ASCENDING = 0, THC_ORDER_SPLIT = 1 };
 
 /* The problem statement of Alg. 3.  Plain data, owned by the caller, read on the host only. */
 typedef struct thc_params {
-  uint64_t d;          /* padded coordinate count per worker; a multiple of `block`                        */
+  uint64_t d;          /* padded coordinate count per worker; a multiple of `block`, below 2^40            */
   uint64_t block;      /* B: RHT block, a power of two, 2^10 <= B <= 2^27, B divides d                     */
   uint32_t n;          /* number of workers, 1 <= n <= THC_MAX_WORKERS                                     */
   uint32_t b;          /* bits per table index, 1..8 (1, 2, 4, 8 have fast paths)                          */

@@ -25,7 +25,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 int validate(const thc_params* p) {
   if (!p) return THC_EINVAL;
   if (p->block < (1ull << 10) || p->block > (1ull << 27) || (p->block & (p->block - 1))) return THC_EINVAL;
-  if (p->d == 0 || p->d % p->block) return THC_EINVAL;
+  if (p->d == 0 || p->d % p->block || p->d >> 40) return THC_EINVAL;   // grids are 32-bit tile counts
   if (p->n < 1) return THC_EINVAL;
   if (p->n > THC_MAX_WORKERS) return THC_EUNSUPPORTED;
   if (p->b < 1 || p->b > 8) return THC_EINVAL;

@@ -85,6 +85,8 @@ def test_workspace_size():
     (dict(table=T430[:-1] + [29]), -2),        # T[last] != g
     (dict(n=9), -3),                           # 30 * 9 = 270 > 255: the prototype's eight-worker limit (Sec. 8 setup)
     (dict(n=16, agg_bits=8), -3),
+    (dict(d=1 << 40, block=1 << 20), -1),      # more tiles than a 32-bit grid index
+    (dict(stage_order=2), -1),
 ])
 def test_validation_codes(kw, code):
     p = _p(**kw)
