@@ -61,6 +61,7 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture one round in a HIP graph and replay it (the round counter then stays fixed): for "
                          "small vectors, where the dozen launches of a round dominate")
+    ap.add_argument("--block-log2", type=int, default=0, help="override the RHT block size (2^10 .. 2^27)")
     ap.add_argument("--agg-bits", type=int, default=0, help="override the width of the aggregated sums (1..16)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device-to-device copy five times and exit (reference for HBM byte counters)")
@@ -96,6 +97,9 @@ def main():
         table = list(range(2 ** w.b))
     if args.agg_bits:
         w = wl.replace(w, agg_bits=args.agg_bits)
+    if args.block_log2:
+        blk = 1 << args.block_log2
+        w = wl.replace(w, block=blk, d=-(-w.d // blk) * blk)
     seed = wl.RHT_SEED
     order = api.THC_ORDER_SPLIT if args.stage_order == "split" else api.THC_ORDER_ASCENDING
     L = api.make_params(w.d, w.block, w.n, w.b, w.g, t_p, seed, table, w.agg_bits,

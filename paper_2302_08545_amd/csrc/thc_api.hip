@@ -335,7 +335,9 @@ int thc_prepare_range(const thc_params* p, uint64_t round, const void* const* gr
   launch_fwd_lo(pl, a, p->in_dtype == THC_DTYPE_BF16, ef != nullptr, tiles_of(p->d), p->n, s);
   if (range_M) {
     RangeArgs r{a.partials, range_M, p->d, p->n, (uint32_t)pl.L, (uint32_t)pl.L1, p->t_p};
-    k_range<<<dim3((unsigned)(p->d / p->block)), dim3(RANGE_NT), 0, s>>>(r);
+    const uint64_t K = p->d / p->block;
+    if (pl.L - pl.L1 <= 3) k_range_small<<<dim3((unsigned)((K + 255) / 256)), dim3(256), 0, s>>>(r);
+    else k_range<<<dim3((unsigned)K), dim3(RANGE_NT), 0, s>>>(r);
   }
   return check_launch();
 }

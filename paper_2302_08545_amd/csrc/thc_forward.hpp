@@ -155,8 +155,30 @@ struct RangeArgs {
 
 constexpr int RANGE_NT = 1024;
 
-// One workgroup per block: Sigma x^2 of every worker in a fixed summation order (thread-strided partial sums,
-// wave butterflies, then the 16 wave totals in sequence), the maximum over workers, and M.
+__device__ __forceinline__ float range_from_sum(double smax, float t_p, uint32_t L) {
+  return (float)(((double)t_p * __builtin_sqrt(smax)) / __builtin_sqrt((double)(1ull << L)));
+}
+
+// Blocks of at most 8 tiles (up to 2^16 coordinates): one thread per block adds the block's partial sums of
+// every worker in index order.
+__global__ __launch_bounds__(256) void k_range_small(const RangeArgs a) {
+  const uint64_t k = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (k >= (a.d >> a.L)) return;
+  const uint32_t ppb = 1u << (a.L - a.L1);
+  const uint64_t per_worker = a.d >> a.L1;
+  double smax = 0.0;
+  for (uint32_t i = 0; i < a.n; ++i) {
+    const double* p = a.partials + (uint64_t)i * per_worker + k * ppb;
+    double s = 0.0;
+    for (uint32_t j = 0; j < ppb; ++j) s += p[j];
+    smax = s > smax ? s : smax;
+  }
+  a.range_M[k] = range_from_sum(smax, a.t_p, a.L);
+}
+
+// Larger blocks: one workgroup per block.  Sigma x^2 of every worker in a fixed summation order
+// (thread-strided partial sums, wave butterflies, then the 16 wave totals in sequence), the maximum over
+// workers, and M.
 __global__ __launch_bounds__(RANGE_NT) void k_range(const RangeArgs a) {
   __shared__ double wsum[MAXW][RANGE_NT / 64];
   const uint64_t k = blockIdx.x;
@@ -178,8 +200,7 @@ __global__ __launch_bounds__(RANGE_NT) void k_range(const RangeArgs a) {
       for (int w = 0; w < RANGE_NT / 64; ++w) s += wsum[i][w];
       smax = s > smax ? s : smax;
     }
-    const double M = ((double)a.t_p * __builtin_sqrt(smax)) / __builtin_sqrt((double)(1ull << a.L));
-    a.range_M[k] = (float)M;
+    a.range_M[k] = range_from_sum(smax, a.t_p, a.L);
   }
 }
 
