@@ -111,12 +111,13 @@ Plan make_plan(uint64_t block, uint32_t stage_order) {
   pl.L = ilog2(block);
   pl.L1 = pl.L < LOG_TILE ? pl.L : LOG_TILE;
   pl.split = stage_order == THC_ORDER_SPLIT && pl.L >= 16;
-  // The bits left after the lo pass go to ceil(rem / 7) strided passes of nearly equal size (wider rows make
-  // longer contiguous segments); the last one, fused with the quantizer or the final scaling, gets the smallest.
-  // In the split order the first of them starts with bits 10, 11, 12: its rows are 1024 coordinates wide at most,
-  // so it must own all three, which any share of at least 3 bits guarantees.
+  // Up to 9 bits left after the lo pass: one strided pass takes them all (8 and 9 bits mean rows of only 128 and
+  // 64 bytes, still far cheaper than another trip through HBM).  More than that: ceil(rem / 7) strided passes of
+  // nearly equal size (wider rows make longer contiguous segments); the last one, fused with the quantizer or
+  // the final scaling, gets the smallest.  In the split order the first of them starts with bits 10, 11, 12: its
+  // rows are 1024 coordinates wide at most, so it must own all three, which any share of at least 3 bits guarantees.
   const int rem = pl.L - pl.L1;
-  const int npass = rem > 0 ? (rem + 6) / 7 : 1;
+  const int npass = rem <= 9 ? 1 : (rem + 6) / 7;
   pl.nmid = npass - 1;
   pl.R = rem / npass;
   for (int m = 0, left = rem - pl.R; m < pl.nmid; ++m) {
@@ -184,6 +185,16 @@ void dispatch_0_7(int r, A&&... args) {
     case 5: Launcher<5>::run(args...); break;
     case 6: Launcher<6>::run(args...); break;
     default: Launcher<7>::run(args...); break;
+  }
+}
+
+// the last pass of a transform may take 8 or 9 bits
+template <template <int> class Launcher, class... A>
+void dispatch_0_9(int r, A&&... args) {
+  switch (r) {
+    case 8: Launcher<8>::run(args...); break;
+    case 9: Launcher<9>::run(args...); break;
+    default: dispatch_0_7<Launcher>(r, args...); break;
   }
 }
 
@@ -265,7 +276,7 @@ void run_inverse(const thc_params* p, const Plan& pl, InvLoArgs lo, float* wsx, 
   hi.d = len;
   hi.tm = pl.hi;
   hi.c = (float)(1.0 / std::sqrt((double)p->block));
-  dispatch_0_7<LaunchInvHi>(pl.R, hi, tiles_of(len), s);
+  dispatch_0_9<LaunchInvHi>(pl.R, hi, tiles_of(len), s);
 }
 
 // Kernels that hand a vector to each other through the workspace (inverse lo -> hi, middle passes, the error-feedback
@@ -392,7 +403,7 @@ int thc_compress(const thc_params* p, uint32_t worker_id, uint64_t round, const 
     q.packed = pk;
     q.d = len;
     q.j0 = base_coord(p) + j0;
-    dispatch_0_7<LaunchQuant>(pl.R, q, (pl.L & 1) == 0, tiles_of(len), s);
+    dispatch_0_9<LaunchQuant>(pl.R, q, (pl.L & 1) == 0, tiles_of(len), s);
     if (ef_inout) {
       lo.src = pk;
       lo.range_M = rM;
@@ -525,7 +536,7 @@ int thc_uniform_prepare_range(const thc_params* p, uint64_t round, const void* c
       run_mids(pl, wsx, p->d, s);
       HiStoreArgs h{wsx, pmin + i * per_worker, pmax + i * per_worker, p->d, pl.hi, (uint32_t)pl.L,
                     (float)(1.0 / std::sqrt((double)p->block))};
-      dispatch_0_7<LaunchHiStore>(pl.R, h, tiles_of(p->d), s);
+      dispatch_0_9<LaunchHiStore>(pl.R, h, tiles_of(p->d), s);
     }
   } else {
     MinMaxArgs a{};

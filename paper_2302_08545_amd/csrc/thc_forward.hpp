@@ -222,15 +222,17 @@ struct HiGeom {
 
 // Front half of a strided pass with R >= 2 row bits (no bounds checks: such tiles are always whole).
 // Each thread loads four rows (4 rho + 0..3) of four consecutive columns, finishes row bits 0 and 1 in
-// registers, parks the tile in LDS (row-major, no padding) and runs row bits [2, 2 + NB1) as one LDS
-// round.  What is left is NB2 = R - 2 - NB1 (0 or 1) top bits for the caller's epilogue.
+// registers, parks the tile in LDS (row-major, no padding) and runs row bits [2, 2 + NB1) through LDS: one
+// round of up to four bits for R <= 7, which leaves NB2 = R - 2 - NB1 (0 or 1) top bits for the caller's
+// epilogue; two rounds and nothing left for R = 8 and 9 (rows of 128 and 64 bytes: blocks of 2^21 and 2^22
+// coordinates then need no pass in between).
 template <int R>
 struct HiSplit {
   static constexpr int LOGW = LOG_TILE - R;
   static constexpr int W = 1 << LOGW;
-  static constexpr int NB1 = (R - 2) < 4 ? (R - 2) : 4;
+  static constexpr int NB1 = R > 7 ? R - 2 : ((R - 2) < 4 ? (R - 2) : 4);
   static constexpr int NB2 = R - 2 - NB1;
-  static_assert(R >= 2 && R <= 7 && NB2 <= 1, "strided pass handles 2..7 row bits");
+  static_assert(R >= 2 && R <= 9 && NB2 <= 1, "strided pass handles 2..9 row bits");
 };
 
 template <int R>

@@ -168,8 +168,17 @@ __global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
 
   if constexpr (R >= 2) {
     hi_front<R>(a.x, g, lds, t);
-    // 32 consecutive tile indices are 32 consecutive coordinates (rows are at least 64 wide)
-    if (t < TILE / 32) sgn[t] = sign_word(a.j0 + g.coord(32 * t), a.round, a.k0, a.k1);
+    // 32 consecutive tile indices are 32 consecutive coordinates, or, with 16-wide rows, two aligned halves
+    if (t < TILE / 32) {
+      if constexpr (HiGeom<R>::W >= 32) {
+        sgn[t] = sign_word(a.j0 + g.coord(32 * t), a.round, a.k0, a.k1);
+      } else {
+        const uint64_t j0 = a.j0 + g.coord(32 * t), j1 = a.j0 + g.coord(32 * t + 16);
+        const uint32_t lo = sign_word(j0 & ~31ull, a.round, a.k0, a.k1) >> (j0 & 31);
+        const uint32_t hi = sign_word(j1 & ~31ull, a.round, a.k0, a.k1) >> (j1 & 31);
+        sgn[t] = (lo & 0xFFFFu) | (hi << 16);
+      }
+    }
     int idx[2];
     float v[2][8];
     hi_back<R>(lds, t, idx, v);

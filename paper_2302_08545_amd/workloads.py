@@ -164,11 +164,11 @@ def bytes_per_coord(w: Workload) -> float:
 def moved_bytes_per_coord(w: Workload) -> float:
     """HBM bytes per (padded) coordinate the kernels actually move in one full round: every pass of a transform
     reads and writes the vector once (rocprofv3's FETCH_SIZE / WRITE_SIZE read exactly this on the VGG16-shaped
-    workload).  A transform of 2^L coordinates takes the first pass, ceil((L - 13) / 7) - 1 middle passes (0 up
-    to L = 20) and the last pass."""
+    workload).  A transform of 2^L coordinates takes the first pass (13 bits), the last pass (up to 9 bits) and,
+    above L = 22, ceil((L - 13) / 7) - 2 passes in between."""
     in_b = 4 if w.dtype == "f32" else 2
     L = w.block.bit_length() - 1
-    mids = max(0, -(-(L - 13) // 7) - 1)
+    mids = 0 if L - 13 <= 9 else -(-(L - 13) // 7) - 1
     fwd = (in_b + (4 if w.ef else 0) + 4) + 8 * mids + (4 + w.b / 8)
     ef = (w.b / 8 + 4) + 8 * mids + (4 + in_b + 4 + 4) if w.ef else 0
     agg = w.n * w.b / 8 + w.agg_bits / 8
