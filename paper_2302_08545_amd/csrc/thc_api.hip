@@ -146,6 +146,19 @@ Plan make_plan(uint64_t block, uint32_t stage_order) {
   return pl;
 }
 
+// Tiling of the first pass over `len` coordinates.  Consecutive 8192-coordinate tiles (ascending order, or blocks
+// below 2^16) stream faster (measured: 5.7 against 5.3 TB/s) when the tile order is permuted inside spans of at least
+// 2^19 coordinates so that the low three bits of the tile index, i.e. the XCD, select offset bits 16..18 rather
+// than 13..15.  Vectors that are not whole spans keep the natural order.
+TileMap lo_tilemap(const Plan& pl, uint64_t len) {
+  if (pl.split) return pl.lo;
+  const int span = pl.L < 19 ? 19 : pl.L;
+  if (len & ((1ull << span) - 1)) return pl.lo;
+  const int far[3] = {16, 17, 18};
+  const TileMap m = make_tilemap(span, LOG_TILE, {}, far);
+  return m.L ? m : pl.lo;
+}
+
 size_t partial_count(const thc_params* p, const Plan& pl) { return (size_t)p->n * (size_t)(p->d >> pl.L1); }
 
 size_t ws_x_bytes(const thc_params* p) { return (size_t)p->n * (size_t)p->d * sizeof(float); }
@@ -267,7 +280,7 @@ void run_mids(const Plan& pl, float* x, uint64_t d, hipStream_t s) {
 // inverse transform of `len` coordinates that k_inv_lo is about to produce in `wsx`
 void run_inverse(const thc_params* p, const Plan& pl, InvLoArgs lo, float* wsx, InvHiArgs hi, uint64_t len,
                  hipStream_t s) {
-  lo.tm = pl.lo;
+  lo.tm = lo_tilemap(pl, len);
   lo.ws_x = wsx;
   lo.d = len;
   launch_inv_lo(pl, lo, tiles_of(len), s);
@@ -342,7 +355,7 @@ int thc_prepare_range(const thc_params* p, uint64_t round, const void* const* gr
   a.round = (uint32_t)round;
   a.k0 = (uint32_t)p->seed;
   a.k1 = (uint32_t)(p->seed >> 32);
-  a.tm = pl.lo;
+  a.tm = lo_tilemap(pl, p->d);
   launch_fwd_lo(pl, a, p->in_dtype == THC_DTYPE_BF16, ef != nullptr, tiles_of(p->d), p->n, s);
   if (range_M) {
     RangeArgs r{a.partials, range_M, p->d, p->n, (uint32_t)pl.L, (uint32_t)pl.L1, p->t_p};

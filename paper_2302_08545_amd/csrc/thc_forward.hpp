@@ -118,7 +118,9 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
       for (int w = 0; w < 4; ++w) s += wsum[t >> 1][4 * (t & 1) + w];
     }
     // one partial per tile (all of it in one block) or, for blocks below 8192, per block of the linear tile
-    const uint64_t pidx = L1 >= LOG_TILE ? (uint64_t)blockIdx.x : (off >> L1) + t;
+    // the row-split tile is not contiguous: its number stands in (the same block either way); a contiguous tile
+    // is numbered by where it lies
+    const uint64_t pidx = XO ? (uint64_t)blockIdx.x : (off >> L1) + t;
     if (pidx < (a.d >> L1)) a.partials[(uint64_t)worker * (a.d >> L1) + pidx] = s;
   }
 

@@ -116,7 +116,9 @@ def to_np32(t):
 
 # ----------------------------------------------------------------------------- individual calls
 @pytest.mark.parametrize("block,K,n", [(1 << 10, 3, 2), (1 << 11, 5, 2), (1 << 12, 4, 3), (1 << 13, 3, 2),
-                                       (1 << 15, 2, 2), (1 << 20, 2, 4)])
+                                       (1 << 15, 2, 2), (1 << 20, 2, 4),
+                                       # whole spans of 2^19 coordinates: the first pass permutes its tile order
+                                       (1 << 12, 128, 2), (1 << 10, 1024, 1), (1 << 15, 48, 1), (1 << 13, 192, 1)])
 def test_prepare_range_and_compress(block, K, n):
     d = block * K
     P, L = both_params(d, block, n)
@@ -169,7 +171,8 @@ def test_aggregate_all_top_indices_reach_g_times_n():
 
 
 @pytest.mark.parametrize("block,K,agg_bits,n", [(1 << 10, 3, 8, 4), (1 << 12, 2, 16, 12), (1 << 13, 2, 8, 8), (1 << 16, 2, 8, 2),
-                                                (1 << 20, 1, 8, 8), (1 << 11, 3, 7, 4), (1 << 13, 2, 9, 16), (1 << 14, 1, 12, 40)])
+                                                (1 << 20, 1, 8, 8), (1 << 11, 3, 7, 4), (1 << 13, 2, 9, 16), (1 << 14, 1, 12, 40),
+                                                (1 << 11, 512, 8, 3), (1 << 14, 96, 8, 2)])
 def test_decompress(block, K, agg_bits, n):
     d = block * K
     P, L = both_params(d, block, n, agg_bits=agg_bits)
