@@ -51,6 +51,14 @@ __device__ __forceinline__ uint64_t tm_base(const TileMap& m, uint32_t tile) {
   return ((uint64_t)(tile >> m.nfixed) << m.L) | off;
 }
 
+// Kernels that walk a vector in consecutive 8192-coordinate tiles, one per workgroup: workgroup ids are dealt
+// round-robin to the 8 XCDs, and streaming is faster (measured 5.7 against 5.3 TB/s) when an XCD keeps to its own
+// value of byte-address bits 18..20 rather than 15..17.  Inside every whole group of 64 tiles the low three bits of
+// the workgroup id therefore select tile bits 3..5.
+__device__ __forceinline__ uint32_t xcd_tile(uint32_t wg, uint32_t ntiles) {
+  return (wg | 63u) < ntiles ? (wg & ~63u) | ((wg & 7u) << 3) | ((wg >> 3) & 7u) : wg;
+}
+
 __device__ __forceinline__ uint32_t tm_row(const TileMap& m, uint32_t r) {
   return ((r & ((1u << m.n0) - 1u)) << m.sh0) | ((r >> m.n0) << m.sh1);
 }

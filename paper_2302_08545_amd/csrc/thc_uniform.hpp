@@ -36,7 +36,7 @@ __global__ __launch_bounds__(NT) void k_minmax(const MinMaxArgs a) {
   __shared__ float smin[32], smax[32];   // one per 256 consecutive coordinates of the tile
   const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
   const uint32_t worker = blockIdx.y;
-  const uint64_t off = (uint64_t)blockIdx.x << LOG_TILE;
+  const uint64_t off = (uint64_t)xcd_tile(blockIdx.x, gridDim.x) << LOG_TILE;
   const float* ef = EF ? static_cast<const float*>(a.efs.p[worker]) : nullptr;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(NT) void k_uniform_quant(const UQuantArgs a) {
   __shared__ uint4 lut[256];
   __shared__ float sM[8], sLo[8], sScale[8], sStep[8];
   const int t = threadIdx.x;
-  const uint64_t off = (uint64_t)blockIdx.x << LOG_TILE;
+  const uint64_t off = (uint64_t)xcd_tile(blockIdx.x, gridDim.x) << LOG_TILE;
   if (t < 256) {
     lut[t] = quant_lut_entry(a.lut[t]);
   }
