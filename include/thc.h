@@ -163,6 +163,22 @@ int thc_uniform_decompress(const thc_params* p, uint64_t round, const void* agg,
 
 /* ---- host-side helpers (no GPU work) ------------------------------------------------------------- */
 
+/* Introspection for tests and tools: how the Hadamard transform of these parameters is cut into passes over
+ * HBM and how every pass tiles a block.  Returns the number of passes (2 to 5), or a negative status; with
+ * out != NULL it also writes one record of THC_PLAN_RECORD_WORDS 32-bit words per pass (cap_records must be at
+ * least the number of passes).  Record layout (unused words are 0xFFFFFFFF):
+ *   [0]      0 = first pass on 8192 consecutive coordinates, 3 = first pass on 8 rows of 1024 coordinates
+ *            (rows at offset bits 13..15), 1 = strided pass in place, 2 = last strided pass
+ *   [1]      number of butterfly stages of the pass;  [2 .. 2+n)  their offset bits, in processing order
+ *   [18..37) the tiling: L (log2 of the span the tile index runs over), log2 of the row length, number of row
+ *            bits, number of tile-index bits, then the row index as two runs (length of the first run, target
+ *            bit of the first run, target bit of the rest), then up to four runs of tile-index bits:
+ *            4 x first tile-index bit, 4 x mask, 4 x target offset bit.
+ * The offset of a coordinate inside its span is  sum_i ((tile >> first_i) & mask_i) << target_i  (tile index bits)
+ * | row bits | column. */
+enum { THC_PLAN_RECORD_WORDS = 40 };
+int thc_describe_plan(const thc_params* p, uint32_t* out /* host, or NULL */, size_t cap_records);
+
 /* t_p = Phi^-1(1 - p/2) (Sec. 5.1), 0 < p < 1. */
 double thc_threshold(double p);
 

@@ -15,7 +15,8 @@ THC_ORDER_ASCENDING, THC_ORDER_SPLIT = 0, 1
 
 EXPORTS = ("thc_version", "thc_strerror", "thc_workspace_bytes", "thc_prepare_range", "thc_compress",
            "thc_aggregate", "thc_decompress", "thc_uniform_prepare_range", "thc_uniform_compress",
-           "thc_uniform_decompress", "thc_threshold", "thc_solve_table", "thc_solve_table_bruteforce")
+           "thc_uniform_decompress", "thc_threshold", "thc_solve_table", "thc_solve_table_bruteforce",
+           "thc_describe_plan")
 
 
 class thc_params(C.Structure):
@@ -57,6 +58,7 @@ def lib():
         L.thc_solve_table.argtypes = [u32, u32, C.c_double, C.POINTER(C.c_uint8), C.POINTER(C.c_double)]
         L.thc_solve_table_bruteforce.argtypes = [u32, u32, C.c_double, C.POINTER(C.c_uint8), C.POINTER(C.c_double),
                                                  C.POINTER(C.c_uint64)]
+        L.thc_describe_plan.argtypes = [pp, C.POINTER(C.c_uint32), C.c_size_t]
         _LIB = L
     return _LIB
 
@@ -172,3 +174,23 @@ def thc_solve_table_bruteforce(b: int, g: int, p: float):
     count = C.c_uint64(0)
     _check(lib().thc_solve_table_bruteforce(b, g, p, out, C.byref(cost), C.byref(count)), "thc_solve_table_bruteforce")
     return [int(out[i]) for i in range(2 ** b)], cost.value, count.value
+
+
+THC_PLAN_RECORD_WORDS = 40
+
+
+def thc_describe_plan(p: thc_params):
+    """The passes of the transform for these parameters: a list of dicts (kind, bits, tiling fields)."""
+    n = lib().thc_describe_plan(C.byref(p), None, 0)
+    _check(min(n, 0), "thc_describe_plan")
+    buf = (C.c_uint32 * (n * THC_PLAN_RECORD_WORDS))()
+    _check(min(lib().thc_describe_plan(C.byref(p), buf, n), 0), "thc_describe_plan")
+    names = ("L", "logw", "nrows", "nfixed", "n0", "sh0", "sh1")
+    out = []
+    for k in range(n):
+        r = buf[k * THC_PLAN_RECORD_WORDS:(k + 1) * THC_PLAN_RECORD_WORDS]
+        rec = {"kind": r[0], "bits": list(r[2:2 + r[1]])}
+        rec.update(zip(names, r[18:25]))
+        rec["fcum"], rec["fmask"], rec["fpos"] = list(r[25:29]), list(r[29:33]), list(r[33:37])
+        out.append(rec)
+    return out

@@ -55,6 +55,7 @@ struct Plan {
   int nmid;
   int mid[3];       // bit counts of the in-place middle passes
   int R;            // the last pass does R bits
+  int bits[4][16];  // the butterfly bits of every pass after the first, in processing order (mids, then the last)
   TileMap lo, midmap[3], hi;
   bool ok() const {
     if (!lo.L || !hi.L) return false;
@@ -138,10 +139,12 @@ Plan make_plan(uint64_t block, uint32_t stage_order) {
   size_t at = 0;
   for (int m = 0; m < pl.nmid; ++m) {
     std::vector<int> rows(todo.begin() + at, todo.begin() + at + pl.mid[m]);
+    std::copy(rows.begin(), rows.end(), pl.bits[m]);
     pl.midmap[m] = make_tilemap(Lg, LOG_TILE - pl.mid[m], rows, pl.split ? grp : low);
     at += pl.mid[m];
   }
   std::vector<int> rows(todo.begin() + at, todo.end());
+  std::copy(rows.begin(), rows.end(), pl.bits[pl.nmid]);
   pl.hi = make_tilemap(Lg, LOG_TILE - pl.R, rows, pl.split ? grp : low);
   return pl;
 }
@@ -329,6 +332,33 @@ int thc_workspace_bytes(const thc_params* p, size_t* bytes_out) {
   const Plan pl = make_plan(p->block, p->stage_order);
   *bytes_out = ws_x_bytes(p) + partial_count(p, pl) * (sizeof(double) + 2 * sizeof(float)) + 256;
   return THC_OK;
+}
+
+int thc_describe_plan(const thc_params* p, uint32_t* out, size_t cap_records) {
+  const int rc = validate(p);
+  if (rc) return rc;
+  const Plan pl = make_plan(p->block, p->stage_order);
+  if (!pl.ok()) return THC_EUNSUPPORTED;
+  const int npass = 2 + pl.nmid;
+  if (!out) return npass;
+  if (cap_records < (size_t)npass) return THC_EINVAL;
+  auto put = [&](int rec, uint32_t kind, const int* bits, int nbits, const TileMap& m) {
+    uint32_t* r = out + (size_t)rec * THC_PLAN_RECORD_WORDS;
+    std::fill(r, r + THC_PLAN_RECORD_WORDS, 0xFFFFFFFFu);
+    r[0] = kind;
+    r[1] = (uint32_t)nbits;
+    for (int i = 0; i < nbits; ++i) r[2 + i] = (uint32_t)bits[i];
+    const uint32_t tm[19] = {m.L, m.logw, m.nrows, m.nfixed, m.n0, m.sh0, m.sh1, m.fcum[0], m.fcum[1], m.fcum[2],
+                             m.fcum[3], m.fmask[0], m.fmask[1], m.fmask[2], m.fmask[3], m.fpos[0], m.fpos[1],
+                             m.fpos[2], m.fpos[3]};
+    std::copy(tm, tm + 19, r + 18);
+  };
+  int first[16];
+  for (int i = 0; i < pl.L1; ++i) first[i] = (pl.split && i >= 10) ? i + 3 : i;
+  put(0, pl.split ? 3u : 0u, first, pl.L1, lo_tilemap(pl, p->d));
+  for (int m = 0; m < pl.nmid; ++m) put(1 + m, 1u, pl.bits[m], pl.mid[m], pl.midmap[m]);
+  put(npass - 1, 2u, pl.bits[pl.nmid], pl.R, pl.hi);
+  return npass;
 }
 
 int thc_prepare_range(const thc_params* p, uint64_t round, const void* const* grads, const float* const* ef,
