@@ -428,6 +428,35 @@ def test_a_round_captured_in_a_hip_graph_replays_bit_for_bit():
         del scratch
 
 
+def test_homomorphism_on_the_library_itself():
+    """Sec. 4.3's defining property, on the GPU alone: decompressing the aggregate of all workers equals the average
+    of what each worker's stream decompresses to on its own (same table, same range), up to binary32 rounding."""
+    block, K, n = 1 << 16, 4, 8
+    d = block * K
+    _, L = both_params(d, block, n, order=1)
+    grads = [x.to(DEV) for x in make_grads(d, n, seed=12)]
+    R = GpuRound(L)
+    R.prepare(9, grads)
+    R.compress_all(9, grads)
+    R.aggregate()
+    R.decompress(9)
+    together = R.out.double().cpu().numpy()
+    _, L1 = both_params(d, block, 1, order=1)                 # one worker at a time: Y = T[Z_i], n = 1
+    S = GpuRound(L1)
+    mean = np.zeros(d, dtype=np.float64)
+    for i in range(n):
+        api.thc_aggregate(L1, [R.packed[i]], S.agg)
+        api.thc_decompress(L1, 9, S.agg, R.range_M, S.out, S.ws)
+        mean += S.out.double().cpu().numpy()
+    mean /= n
+    assert rel_l2(together, mean) <= 1e-6
+    # and it estimates the true mean of the inputs.  Every worker's error is about 0.02 ||x_max||^2 (the table's cost
+    # for the shared range), the workers here have norms 1 : 1.3 : ... : 3.1, so the mean's NMSE stays below
+    # 0.02 * n * 3.1^2 / sum_i (1 + 0.3 i)^2 = 0.042
+    true = np.mean([g.double().cpu().numpy() for g in grads], axis=0)
+    assert 0.005 < o.nmse(true, together) < 0.045
+
+
 # ----------------------------------------------------------------------------- slices of a longer vector
 @pytest.mark.parametrize("first_block,block,K,n,ef,order", [(5, 1 << 12, 3, 2, True, 0), (1 << 25, 1 << 10, 4, 2, False, 0),
                                                             (3, 1 << 16, 2, 2, True, 1), (4000, 1 << 21, 1, 1, True, 1)])
