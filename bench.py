@@ -23,7 +23,7 @@ HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E
 # runs of this file (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled by what the same counter
 # reads for the plain 1 GiB copy of --calibrate-copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).
 # Summary and commands: profiles/k_fwd_lo_c3_vgg16_hbm_bytes.txt
-MEASURED_TRAFFIC_BYTES = {"c3_vgg16": (4194371.7 * 2.0 + 8397282.5 * 1.0) * 1024.0}
+MEASURED_TRAFFIC_BYTES = {"c3_vgg16": (4194371.2 * 2.0 + 8397262.9 * 1.0) * 1024.0}
 
 
 def cpu_baseline(w, table, t_p, seed, order=0, budget_blocks=8):
