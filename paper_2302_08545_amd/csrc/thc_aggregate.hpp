@@ -202,4 +202,60 @@ __global__ __launch_bounds__(256) void k_aggregate_b2w8(const AggB2Args a) {
   }
 }
 
+// 4-bit indices -> sums of any other width W (the exact width ceil(log2(g n + 1)) of Sec. 8.4, say).  Sums are
+// formed as in k_aggregate_b4w16; a thread's 32 fields make exactly W dwords, which go through LDS so that the
+// workgroup writes its 1024 * W bytes as consecutive 16-byte vectors.
+template <int W>
+__global__ __launch_bounds__(256) void k_aggregate_b4wx(const AggB4W16Args a) {
+  __shared__ __align__(16) uint32_t stage[256 * W];
+  const int t = threadIdx.x;
+  const uint64_t v0 = (uint64_t)blockIdx.x * 256;
+  const uint64_t v = v0 + t;
+  if (v < a.nvec) {
+    const uint32_t tb[4] = {a.tb[0], a.tb[1], a.tb[2], a.tb[3]};
+    uint32_t acc[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0;
+    for (uint32_t i0 = 0; i0 < a.n; i0 += a.chunk) {
+      const uint32_t i1 = (i0 + a.chunk < a.n) ? i0 + a.chunk : a.n;
+      uint32_t ev[4] = {0, 0, 0, 0}, od[4] = {0, 0, 0, 0};
+      for (uint32_t i = i0; i < i1; ++i) {
+        const uint4 r = reinterpret_cast<const uint4*>(a.packed.p[i])[v];
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          ev[k] += lut16x4(w[k] & 0x0F0F0F0Fu, tb);
+          od[k] += lut16x4((w[k] >> 4) & 0x0F0F0F0Fu, tb);
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        acc[4 * k + 0] += __builtin_amdgcn_perm(od[k], ev[k], 0x0C040C00u);
+        acc[4 * k + 1] += __builtin_amdgcn_perm(od[k], ev[k], 0x0C050C01u);
+        acc[4 * k + 2] += __builtin_amdgcn_perm(od[k], ev[k], 0x0C060C02u);
+        acc[4 * k + 3] += __builtin_amdgcn_perm(od[k], ev[k], 0x0C070C03u);
+      }
+    }
+    // field e = coordinate e of the thread's 32: low or high half of acc[e / 2]; bits [e W, e W + W) of the output
+    uint32_t out[W];
+#pragma unroll
+    for (int k = 0; k < W; ++k) out[k] = 0;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+      const uint32_t f = (e & 1) ? acc[e >> 1] >> 16 : acc[e >> 1] & 0xFFFFu;
+      const int pos = e * W, k = pos >> 5, sh = pos & 31;
+      out[k] |= f << sh;
+      if (sh + W > 32) out[k + 1] |= f >> (32 - sh);
+    }
+#pragma unroll
+    for (int k = 0; k < W; ++k) stage[t * W + k] = out[k];
+  }
+  __syncthreads();
+  const uint64_t left = a.nvec - v0;                       // threads of this workgroup that own coordinates
+  const uint32_t nvec4 = (uint32_t)(left < 256 ? left : 256) * W / 4;   // a multiple of 8 W / 4: nvec is a multiple of 32
+  uint4* dst = reinterpret_cast<uint4*>(a.out + v0 * 4 * W);
+  const uint4* src = reinterpret_cast<const uint4*>(stage);
+  for (uint32_t i = t; i < nvec4; i += 256) dst[i] = src[i];
+}
+
 }  // namespace thc

@@ -483,7 +483,7 @@ int thc_aggregate(const thc_params* p, const uint8_t* const* packed, void* agg_o
     a.n = p->n;
     std::memcpy(&a.tb, p->table, 4);
     k_aggregate_b2w8<<<dim3((unsigned)((a.nvec + 255) / 256)), dim3(256), 0, s>>>(a);
-  } else if (p->b == 4 && p->agg_bits == 16) {
+  } else if (p->b == 4) {
     AggB4W16Args a{};
     for (uint32_t i = 0; i < p->n; ++i) a.packed.p[i] = packed[i];
     a.out = static_cast<uint8_t*>(agg_out);
@@ -491,7 +491,15 @@ int thc_aggregate(const thc_params* p, const uint8_t* const* packed, void* agg_o
     a.n = p->n;
     a.chunk = 255u / p->g;              // g <= 255, so at least one worker per run
     std::memcpy(a.tb, p->table, 16);
-    k_aggregate_b4w16<<<dim3((unsigned)((a.nvec + 255) / 256)), dim3(256), 0, s>>>(a);
+    const dim3 grid((unsigned)((a.nvec + 255) / 256)), blk(256);
+    switch (p->agg_bits) {
+      case 16: k_aggregate_b4w16<<<grid, blk, 0, s>>>(a); break;
+#define THC_AGG_WX(W) case W: k_aggregate_b4wx<W><<<grid, blk, 0, s>>>(a); break;
+      THC_AGG_WX(4) THC_AGG_WX(5) THC_AGG_WX(6) THC_AGG_WX(7) THC_AGG_WX(9) THC_AGG_WX(10) THC_AGG_WX(11)
+      THC_AGG_WX(12) THC_AGG_WX(13) THC_AGG_WX(14) THC_AGG_WX(15)
+#undef THC_AGG_WX
+      default: return THC_EINVAL;       // 4-bit tables reach at least g = 15: the sums need 4 bits or more
+    }
   } else {
     AggArgs a{};
     for (uint32_t i = 0; i < p->n; ++i) a.packed.p[i] = packed[i];

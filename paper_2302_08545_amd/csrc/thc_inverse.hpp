@@ -35,6 +35,33 @@ __device__ __forceinline__ void codes_load(const uint8_t* s8, uint32_t bits, uin
   }
 }
 
+// Sixteen W-bit fields out of a staged bit stream: they start at `first`, or 16 bits into it (`half`).  W is a
+// compile-time constant so that every field's word and shift are; one dword of slack is read past the fields.
+template <int W>
+__device__ __forceinline__ void cut16(const uint32_t* first, bool half, uint32_t (&y)[16]) {
+  constexpr int NW = (16 * W + 31) / 32;          // dwords the fields span when they start on a boundary
+  uint32_t d[NW + 1];
+#pragma unroll
+  for (int k = 0; k <= NW; ++k) d[k] = first[k];
+  if (half) {
+#pragma unroll
+    for (int k = 0; k < NW; ++k) d[k] = __builtin_amdgcn_alignbit(d[k + 1], d[k], 16);
+  }
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    constexpr uint32_t mask = (1u << W) - 1u;
+    const int k = (e * W) >> 5, sh = (e * W) & 31;
+    uint32_t v = d[k] >> sh;
+    if (sh + W > 32) v |= d[k + 1] << (32 - sh);
+    y[e] = v & mask;
+  }
+}
+
+// widths that codes_load / codes_decode take straight from global memory
+__device__ __forceinline__ bool codes_fast_width(uint32_t bits) {
+  return bits == 8 || bits == 16 || bits == 4 || bits == 2 || bits == 1;
+}
+
 __device__ __forceinline__ void codes_decode(uint32_t bits, bool ok, const uint32_t (&w)[8], uint32_t (&y)[16]) {
   if (bits == 8) {
 #pragma unroll
@@ -93,7 +120,27 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
   // raw bits first, so the load is in flight while the block constants are prepared
   uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   uint32_t y[16];
-  if (ok) codes_load(static_cast<const uint8_t*>(a.src), a.src_bits, j, w, y);
+  const bool staged = !codes_fast_width(a.src_bits);
+  if (!staged) {
+    if (ok) codes_load(static_cast<const uint8_t*>(a.src), a.src_bits, j, w, y);
+  } else {
+    // Any other width: the tile's eight runs of 1024 codes (128 * bits bytes each, dword aligned) are copied
+    // into the still unused tile buffer with coalesced loads; every thread then cuts its sixteen fields out.
+    uint32_t* stage = reinterpret_cast<uint32_t*>(lds);
+    const uint32_t per_row = 32u * a.src_bits;                       // dwords per 1024 codes: fewer than NT
+    if ((uint32_t)t < per_row) {
+      uint32_t val[8];
+#pragma unroll
+      for (uint32_t r = 0; r < 8; ++r) {
+        const uint64_t jr = off + lo_map<XO>(1024u * r);             // first coordinate of the run
+        val[r] = 0;
+        if (!GUARD || jr < a.d)                                      // runs exist whole or not at all: 1024 divides d
+          val[r] = reinterpret_cast<const uint32_t*>(static_cast<const uint8_t*>(a.src) + (jr >> 3) * a.src_bits)[t];
+      }
+#pragma unroll
+      for (uint32_t r = 0; r < 8; ++r) stage[r * per_row + t] = val[r];
+    }
+  }
 
   const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
   if (t < nblk) {
@@ -106,7 +153,26 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
   if (a.use_table && t < 256) tabf[t] = (float)a.table[t];
   __syncthreads();
 
-  codes_decode(a.src_bits, ok, w, y);
+  if (!staged) {
+    codes_decode(a.src_bits, ok, w, y);
+  } else {
+    // sixteen fields start at bit 16 * (field number / 16) * bits of the run: on a dword boundary or in its middle
+    const uint32_t* stage = reinterpret_cast<const uint32_t*>(lds);
+    const uint32_t pos = (uint32_t)(idx & 1023) * a.src_bits;
+    const uint32_t* first = stage + (uint32_t)(idx >> 10) * 32u * a.src_bits + (pos >> 5);
+    switch (a.src_bits) {
+#define THC_CUT(W) case W: cut16<W>(first, (pos & 16u) != 0, y); break;
+      THC_CUT(3) THC_CUT(5) THC_CUT(6) THC_CUT(7) THC_CUT(9) THC_CUT(10) THC_CUT(11) THC_CUT(12) THC_CUT(13)
+      THC_CUT(14) THC_CUT(15)
+#undef THC_CUT
+      default: break;
+    }
+    if (!ok) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) y[e] = 0;
+    }
+    __syncthreads();                                                 // every field is out before the tile is written
+  }
   const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
   const float lo = sM[bt], step = sStep[bt];
   float v[16];
