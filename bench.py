@@ -26,7 +26,7 @@ HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E
 MEASURED_TRAFFIC_BYTES = {"c3_vgg16": (4194371.2 * 2.0 + 8397262.9 * 1.0) * 1024.0}
 
 
-def cpu_baseline(w, table, t_p, seed, order=0, budget_blocks=8):
+def cpu_baseline(w, table, t_p, seed, order=0, budget_blocks=16):
     """The oracle as it stands, timed on the host on a bounded sample: the first block(s) of the same
     workload, all n workers, one full round."""
     import numpy as np
