@@ -63,6 +63,10 @@ def main():
                          "small vectors, where the dozen launches of a round dominate")
     ap.add_argument("--block-log2", type=int, default=0, help="override the RHT block size (2^10 .. 2^27)")
     ap.add_argument("--agg-bits", type=int, default=0, help="override the width of the aggregated sums (1..16)")
+    ap.add_argument("--calls", choices=("all", "each"), default="all",
+                    help="all: thc_compress_all (range and the n workers' streams in one sweep, the headline).  "
+                         "each: thc_prepare_range, then thc_compress once per worker")
+    ap.add_argument("--group-log2", type=int, default=0, help="thc_params.group_log2 (0 = the library's default)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device-to-device copy five times and exit (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -103,11 +107,12 @@ def main():
     seed = wl.RHT_SEED
     order = api.THC_ORDER_SPLIT if args.stage_order == "split" else api.THC_ORDER_ASCENDING
     L = api.make_params(w.d, w.block, w.n, w.b, w.g, t_p, seed, table, w.agg_bits,
-                        api.THC_DTYPE_BF16 if w.dtype == "bf16" else api.THC_DTYPE_F32, order)
+                        api.THC_DTYPE_BF16 if w.dtype == "bf16" else api.THC_DTYPE_F32, order, 0, args.group_log2)
 
     grads = [wl.gradient(w, i, device=dev) for i in range(w.n)]
     efs = [torch.zeros(w.d, dtype=torch.float32, device=dev) for _ in range(w.n)] if w.ef else None
-    ws = torch.empty(api.thc_workspace_bytes(L), dtype=torch.uint8, device=dev)
+    ws_bytes = (api.thc_uniform_workspace_bytes(L, rotate) if uniform else api.thc_workspace_bytes(L, w.ef))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     range_M = torch.zeros(w.K, dtype=torch.float32, device=dev)
     range_m = torch.zeros(w.K, dtype=torch.float32, device=dev)
     packed = [torch.zeros(w.d * w.b // 8, dtype=torch.uint8, device=dev) for _ in range(w.n)]
@@ -124,16 +129,19 @@ def main():
             ev[0].record()
         if uniform:
             api.thc_uniform_prepare_range(L, rnd, grads, efs, rotate, range_m, range_M, ws)
-        else:
-            api.thc_prepare_range(L, rnd, grads, efs, range_M, ws)
+        elif args.calls == "each":
+            api.thc_prepare_range(L, grads, efs, range_M, ws)
         if timed:
             ev[1].record()
-        for i in range(w.n):
-            ef_i = None if efs is None else efs[i]
-            if uniform:
-                api.thc_uniform_compress(L, i, rnd, grads[i], ef_i, rotate, range_m, range_M, packed[i], ws)
-            else:
-                api.thc_compress(L, i, rnd, grads[i], ef_i, range_M, packed[i], ws)
+        if uniform:
+            for i in range(w.n):
+                api.thc_uniform_compress(L, i, rnd, grads[i], None if efs is None else efs[i], rotate, range_m, range_M,
+                                         packed[i], ws)
+        elif args.calls == "each":
+            for i in range(w.n):
+                api.thc_compress(L, i, rnd, grads[i], None if efs is None else efs[i], range_M, packed[i], ws)
+        else:
+            api.thc_compress_all(L, rnd, grads, efs, range_M, packed, ws)
         if timed:
             ev[2].record()
         api.thc_aggregate(L, packed, agg)
@@ -181,10 +189,11 @@ def main():
                 for k, name in enumerate(stage_names)}
     bpc = wl.bytes_per_coord(w)
     in_bytes = 4 if w.dtype == "f32" else 2
-    # Dominant kernel: the forward "lo" pass inside thc_prepare_range (one launch covers all n workers).
-    # Its algorithmic bytes are the gradients (and error-feedback buffers) it must read once.
-    lo_alg_bytes = w.n * w.d * (in_bytes + (4 if w.ef else 0))
-    lo_ms = stage_ms["prepare_range"]
+    # Dominant part: the forward sweep (per group of blocks: first pass of all workers, range, last pass + quantizer
+    # of all workers [+ the error-feedback inverse]).  Its algorithmic bytes: every gradient (and error-feedback
+    # buffer) read once, the error-feedback buffer written once, the packed indices written once.
+    lo_alg_bytes = w.n * w.d * (in_bytes + (8 if w.ef else 0) + w.b / 8)
+    lo_ms = stage_ms["prepare_range"] + stage_ms["compress"]
     achieved = lo_alg_bytes / (lo_ms * 1e-3) / 1e9
     result = {
         "metric": "gradient coords/s (compress+aggregate+decompress)",
@@ -211,7 +220,7 @@ def main():
         "moved_hbm_GBps": wl.moved_bytes_per_coord(w) * w.d / (dt / args.steps) / 1e9,
         "moved_hbm_frac": wl.moved_bytes_per_coord(w) * w.d / (dt / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "stage_ms": stage_ms,
-        "roofline": {"bound": "hbm", "kernel": "k_fwd_lo (thc_prepare_range)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "forward sweep (k_fwd_lo + k_range + k_fwd_hi_quant per group)", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "algorithmic_bytes": lo_alg_bytes, "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
     }

@@ -1,16 +1,18 @@
 /*
  * libthc -- Tensor Homomorphic Compression (arXiv 2302.08545), data-parallel hot path for AMD gfx950.
  *
- * One round of the paper's Alg. 3 ("Training with THC") for n workers whose buffers all live on one
- * GPU maps onto four calls:
+ * One round of the paper's Alg. 3 ("Training with THC") maps onto four calls:
  *
- *   thc_prepare_range   preliminary stage: x_i = grad_i + e_i, per-block norms, the first half of the
- *                       randomized Hadamard transform (the paper runs the norm exchange and the RHT in
- *                       parallel), then the shared range M_k = t_p * max_i ||x_i|| / sqrt(B), m_k = -M_k
- *   thc_compress        main stage, worker side: finish RHT, clamp to [-M, M], stochastic quantization
- *                       onto the table's grid, table index, bit-pack; optional error-feedback update
+ *   thc_prepare_range   preliminary stage: x_i = grad_i + e_i, per-block norms ||x_i||, the shared range
+ *                       M_k = t_p * max_i ||x_i|| / sqrt(B), m_k = -M_k
+ *   thc_compress        main stage, one worker: RHT, clamp to [-M, M], stochastic quantization onto the table's
+ *                       grid, table index, bit-pack; optional error-feedback update
  *   thc_aggregate       main stage, parameter-server side: Y = sum_i T[Z_i] on the packed streams
  *   thc_decompress      worker side: m + (Y/n)(M-m)/g, then the inverse RHT
+ *
+ * and, for n workers whose buffers all live on one GPU, thc_compress_all does the work of thc_prepare_range and of
+ * the n calls of thc_compress in one sweep that reads every gradient once (the paper runs the norm exchange and
+ * the RHT side by side; here the norms come out of the transform's first pass).
  *
  * Conventions
  *   - All data pointers are DEVICE pointers (hipMalloc'd, 16-byte aligned) unless a comment says "host".
@@ -18,13 +20,15 @@
  *   - `stream` is a hipStream_t passed as void*.  Every call validates its arguments on the host,
  *     enqueues its kernels on `stream` and returns without synchronizing.  Calls that share a workspace
  *     must be ordered on one stream (or by events).
- *   - The library allocates nothing and keeps no state: workspace, range, error-feedback buffers, the
- *     round counter and the lookup table are owned by the caller.  Inputs are never modified, except
- *     `ef_inout`.
+ *   - The library allocates nothing and keeps no state, neither on the host nor in the workspace: workspace,
+ *     range, error-feedback buffers, the round counter and the lookup table are owned by the caller, every call
+ *     is complete by itself, and the workspace is scratch whose contents mean nothing between calls.  Inputs are
+ *     never modified, except `ef_inout`.
  *   - Return value: THC_OK (0) or a negative thc_status.  Non-finite inputs (or inputs so large that their
  *     transform overflows binary32) are not detected; they propagate to unspecified (but in-bounds) results.
- *     A block whose range width M - m is below 2^-100 counts as empty: all its indices are 0 and it decodes
- *     to m (this covers the all-zero block, M = 0, which decodes to exact zeros).
+ *     A block whose scale g / (M - m), rounded to binary32, is not a finite number (M = m, or a width below
+ *     about g * 2^-128) counts as empty: all its indices are 0 and it decodes to m (this covers the all-zero
+ *     block, M = 0, which decodes to exact zeros).
  *   - Vector layout: a worker's gradient is one flat vector of d coordinates (padded by the caller with
  *     zeros to a multiple of `block`).  The RHT, the norm and the range are per block of `block`
  *     consecutive coordinates (the paper's 4 MB partition is block = 2^20).
@@ -85,6 +89,10 @@ typedef struct thc_params {
   uint8_t  table[256]; /* T[0 .. 2^b-1]; see thc_solve_table                                               */
   uint32_t stage_order;/* THC_ORDER_ASCENDING or THC_ORDER_SPLIT                                           */
   uint32_t first_block;/* index, in the whole vector, of the first block these buffers hold (0 for a whole vector) */
+  uint32_t group_log2; /* 0 = default (25).  The transform's passes walk a vector in groups of whole blocks of about
+                          2^group_log2 coordinates (over all vectors of the call), 10..40: it sizes the workspace
+                          and decides how much of the intermediate stays in the memory-side cache; never a result */
+  uint32_t reserved;   /* 0 */
 } thc_params;
 
 /* Library version (major*10000 + minor*100 + patch). */
@@ -93,36 +101,43 @@ int thc_version(void);
 /* Human-readable name of a status code (static storage). */
 const char* thc_strerror(int status);
 
-/* Bytes of device workspace the four calls below need for these parameters (host call, no GPU work).
- * The workspace holds the half-rotated vectors of all n workers between thc_prepare_range and
- * thc_compress (n*d binary32 values) plus the partial sums of squares; thc_compress with error feedback and
- * thc_decompress use it as scratch, so its contents are unspecified after them.  Long vectors go through those
- * two in pieces of 2^25 coordinates that share one part of the workspace (it stays in the memory-side cache);
- * the environment variable THC_PIECE_LOG2 changes the piece size, never the results. */
-int thc_workspace_bytes(const thc_params* p, size_t* bytes_out /* host */);
+/* Bytes of device workspace the calls below need for these parameters (host call, no GPU work).  The workspace
+ * holds the half-transformed vectors of one group of blocks (two slots of max(2^group_log2, n * block) binary32
+ * values) and one binary64 partial sum of squares per 8192 coordinates per worker; it does not grow with d beyond
+ * that.  `ef_enabled` says whether error feedback will be used (the update reuses the group's slot, so the size is
+ * the same today; callers should still say). */
+int thc_workspace_bytes(const thc_params* p, int ef_enabled, size_t* bytes_out /* host */);
 
-/* Preliminary stage (Alg. 3: x_i = grad_i + e_i; send ||x_i||, receive the maximum -- in parallel with
- * R_i = RHT(x_i); then M = (t_p / sqrt(d)) * l, m = -M; Sec. 5.3).
- *   round     r of Alg. 3; selects the diagonal D^r.  Must be < 2^32.
+/* Preliminary stage (Alg. 3: x_i = grad_i + e_i; send ||x_i||, receive the maximum; M = (t_p / sqrt(d)) * l,
+ * m = -M; Sec. 5.3).  Reads every gradient once and keeps nothing but range_M.
  *   grads     host array of n device pointers, each d values of in_dtype.
  *   ef        host array of n device pointers to binary32 error-feedback buffers (read only here),
  *             or NULL when error feedback is off.
- *   range_M   device, d/block floats, written: M_k per block (m_k = -M_k).  May be NULL: then only the
- *             half-rotated vectors are produced and the caller supplies its own range to thc_compress.
- *   ws        device workspace of thc_workspace_bytes bytes, written. */
-int thc_prepare_range(const thc_params* p, uint64_t round, const void* const* grads /* host */,
+ *   range_M   device, d/block floats, written: M_k per block (m_k = -M_k).
+ *   ws        device workspace of thc_workspace_bytes bytes (scratch). */
+int thc_prepare_range(const thc_params* p, const void* const* grads /* host */,
                       const float* const* ef /* host or NULL */, float* range_M, void* ws, void* stream);
 
-/* Main stage, worker side (Alg. 3: clamp, Q, SQ, Y_i, Z_i = T^-1[Y_i]; Alg. 2 worker steps; Sec. 4.1).
- * Consumes the half-rotated vector that thc_prepare_range left in `ws` for this worker in this round.
+/* Main stage, one worker (Alg. 3: R = RHT(x), clamp, Q, SQ, Y_i, Z_i = T^-1[Y_i]; Alg. 2 worker steps; Sec. 4.1).
  *   worker_id   < n; selects the rounding stream.
- *   grad        device, the same gradient given to thc_prepare_range (read only when ef_inout != NULL).
- *   ef_inout    device binary32[d] or NULL.  When given: e <- (grad + e) - RHT^-1(X_i) with X_i the
- *               dequantized vector (Alg. 3, error-feedback update).
- *   range_M     device, d/block floats (from thc_prepare_range or from the caller).
- *   packed_out  device, d*b/8 bytes, written. */
+ *   round       r of Alg. 3; selects the diagonal D^r and the rounding draws.  Must be < 2^32.
+ *   grad        device, d values of in_dtype.
+ *   ef_inout    device binary32[d] or NULL.  When given: x = grad + e is what gets compressed, and afterwards
+ *               e <- x - RHT^-1(X_i) with X_i the dequantized vector (Alg. 3, error-feedback update).
+ *   range_M     device, d/block floats (from thc_prepare_range, or the caller's own).
+ *   packed_out  device, d*b/8 bytes, written.
+ *   ws          device workspace (scratch). */
 int thc_compress(const thc_params* p, uint32_t worker_id, uint64_t round, const void* grad,
                  float* ef_inout, const float* range_M, uint8_t* packed_out, void* ws, void* stream);
+
+/* All n workers of one GPU in one sweep: what thc_prepare_range followed by thc_compress(0 .. n-1) computes, bit for
+ * bit, reading every gradient (and error-feedback buffer) once: block group by block group, the transform's first
+ * pass of all workers (with the norms), the range, then the last pass and the quantizer of all workers.
+ *   grads       host array of n device pointers.         ef_inout    host array of n device pointers, or NULL.
+ *   range_M     device, d/block floats, written.         packed_out  host array of n device pointers, written. */
+int thc_compress_all(const thc_params* p, uint64_t round, const void* const* grads /* host */,
+                     float* const* ef_inout /* host or NULL */, float* range_M, uint8_t* const* packed_out /* host */,
+                     void* ws, void* stream);
 
 /* Main stage, PS side (Alg. 2: Y = sum_i T[Z_i]; the PS pseudocode's lookup + aggregate steps).
  *   packed    host array of n device pointers, each d*b/8 bytes.
@@ -143,6 +158,10 @@ int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const f
  * "with rotation" arm of the ablation in App. C): the range is then taken over the rotated vectors.
  * thc_aggregate serves unchanged (with the identity table it sums the indices).  Same pointer, stream,
  * workspace and error conventions as above. */
+
+/* Workspace of the three calls below: min/max partials and, with rotation, the rotated vectors of all n workers
+ * (n * d binary32 values, kept from thc_uniform_prepare_range to thc_uniform_compress). */
+int thc_uniform_workspace_bytes(const thc_params* p, int rotate, size_t* bytes_out /* host */);
 
 /* Preliminary stage of Alg. 1: every worker's min / max, then the global ones.
  *   range_m, range_M   device, d/block floats each, written.

@@ -312,21 +312,19 @@ def unpack_indices(packed: np.ndarray, b: int) -> np.ndarray:
 # --------------------------------------------------------------------------- #
 # Main stage, worker side (Alg. 3: clamp, SQ, Y, Z) and error feedback
 # --------------------------------------------------------------------------- #
-MIN_WIDTH = 2.0 ** -100   # narrower ranges count as empty (see block_scalars)
-
-
 def block_scalars(P: Params, range_M: np.ndarray, range_m: Optional[np.ndarray] = None):
     """Per-block constants derived from the range [m, M] (m = -M unless given), each a binary64 quotient
-    rounded once, with the width M - m taken in binary64:
+    rounded once to binary32, with the width M - m taken in binary64:
     scale = g/(M-m),  step_g = (M-m)/g,  step_n = (M-m)/(g n).
-    An empty range has scale 0, so that every coordinate maps to index 0 (and decodes to m): that covers the
-    all-zero block, and, by this build's choice, every width below 2^-100 (about 8e-31), where g/(M-m) and the
-    products with it leave binary32's normal range."""
+    The grid position of Alg. 2 needs g/(M-m) as a binary32 number.  Where that quotient is not a finite binary32
+    value -- M = m (the all-zero block), or a width so small that it overflows -- the range is empty: scale 0, so
+    that every coordinate maps to index 0 (and decodes to m)."""
     M64 = range_M.astype(np.float64)
     m64 = -M64 if range_m is None else range_m.astype(np.float64)
     W64 = M64 - m64
-    with np.errstate(divide="ignore", invalid="ignore"):
-        scale = np.where(W64 >= MIN_WIDTH, np.float64(P.g) / W64, 0.0).astype(F32)
+    with np.errstate(divide="ignore", invalid="ignore", over="ignore"):
+        scale = (np.float64(P.g) / W64).astype(F32)
+    scale = np.where(np.isfinite(scale), scale, F32(0.0)).astype(F32)
     step_g = (W64 / np.float64(P.g)).astype(F32)
     step_n = (W64 / np.float64(P.g * P.n)).astype(F32)
     return scale, step_g, step_n

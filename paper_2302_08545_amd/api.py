@@ -14,16 +14,16 @@ THC_DTYPE_F32, THC_DTYPE_BF16 = 0, 1
 THC_ORDER_ASCENDING, THC_ORDER_SPLIT = 0, 1
 
 EXPORTS = ("thc_version", "thc_strerror", "thc_workspace_bytes", "thc_prepare_range", "thc_compress",
-           "thc_aggregate", "thc_decompress", "thc_uniform_prepare_range", "thc_uniform_compress",
-           "thc_uniform_decompress", "thc_threshold", "thc_solve_table", "thc_solve_table_bruteforce",
-           "thc_describe_plan")
+           "thc_compress_all", "thc_aggregate", "thc_decompress", "thc_uniform_workspace_bytes",
+           "thc_uniform_prepare_range", "thc_uniform_compress", "thc_uniform_decompress", "thc_threshold",
+           "thc_solve_table", "thc_solve_table_bruteforce", "thc_describe_plan")
 
 
 class thc_params(C.Structure):
     _fields_ = [("d", C.c_uint64), ("block", C.c_uint64), ("n", C.c_uint32), ("b", C.c_uint32),
                 ("g", C.c_uint32), ("agg_bits", C.c_uint32), ("in_dtype", C.c_uint32), ("t_p", C.c_float),
                 ("seed", C.c_uint64), ("table", C.c_uint8 * 256), ("stage_order", C.c_uint32),
-                ("first_block", C.c_uint32)]
+                ("first_block", C.c_uint32), ("group_log2", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class ThcError(RuntimeError):
@@ -45,9 +45,11 @@ def lib():
         L.thc_version.restype = C.c_int
         L.thc_strerror.restype = C.c_char_p
         L.thc_strerror.argtypes = [C.c_int]
-        L.thc_workspace_bytes.argtypes = [pp, C.POINTER(C.c_size_t)]
-        L.thc_prepare_range.argtypes = [pp, u64, C.POINTER(vp), C.POINTER(vp), vp, vp, vp]
+        L.thc_workspace_bytes.argtypes = [pp, C.c_int, C.POINTER(C.c_size_t)]
+        L.thc_uniform_workspace_bytes.argtypes = [pp, C.c_int, C.POINTER(C.c_size_t)]
+        L.thc_prepare_range.argtypes = [pp, C.POINTER(vp), C.POINTER(vp), vp, vp, vp]
         L.thc_compress.argtypes = [pp, u32, u64, vp, vp, vp, vp, vp, vp]
+        L.thc_compress_all.argtypes = [pp, u64, C.POINTER(vp), C.POINTER(vp), vp, C.POINTER(vp), vp, vp]
         L.thc_aggregate.argtypes = [pp, C.POINTER(vp), vp, vp]
         L.thc_decompress.argtypes = [pp, u64, vp, vp, vp, vp, vp]
         L.thc_uniform_prepare_range.argtypes = [pp, u64, C.POINTER(vp), C.POINTER(vp), C.c_int, vp, vp, vp, vp]
@@ -65,10 +67,11 @@ def lib():
 
 def make_params(d: int, block: int, n: int, b: int, g: int, t_p: float, seed: int, table: Sequence[int],
                 agg_bits: int = 8, in_dtype: int = THC_DTYPE_F32, stage_order: int = THC_ORDER_ASCENDING,
-                first_block: int = 0) -> thc_params:
+                first_block: int = 0, group_log2: int = 0) -> thc_params:
     p = thc_params()
     p.stage_order = stage_order
     p.first_block = first_block
+    p.group_log2 = group_log2
     p.d, p.block, p.n, p.b, p.g = d, block, n, b, g
     p.agg_bits, p.in_dtype, p.t_p, p.seed = agg_bits, in_dtype, t_p, seed
     for i, v in enumerate(table):
@@ -109,15 +112,26 @@ def thc_strerror(status: int) -> str:
     return lib().thc_strerror(status).decode()
 
 
-def thc_workspace_bytes(p: thc_params) -> int:
+def thc_workspace_bytes(p: thc_params, ef_enabled: bool = False) -> int:
     out = C.c_size_t(0)
-    _check(lib().thc_workspace_bytes(C.byref(p), C.byref(out)), "thc_workspace_bytes")
+    _check(lib().thc_workspace_bytes(C.byref(p), int(ef_enabled), C.byref(out)), "thc_workspace_bytes")
     return out.value
 
 
-def thc_prepare_range(p: thc_params, rnd: int, grads, ef, range_M, ws, stream=None) -> None:
-    _check(lib().thc_prepare_range(C.byref(p), rnd, _ptr_array(grads), _ptr_array(ef), _ptr(range_M), _ptr(ws),
+def thc_uniform_workspace_bytes(p: thc_params, rotate: bool) -> int:
+    out = C.c_size_t(0)
+    _check(lib().thc_uniform_workspace_bytes(C.byref(p), int(rotate), C.byref(out)), "thc_uniform_workspace_bytes")
+    return out.value
+
+
+def thc_prepare_range(p: thc_params, grads, ef, range_M, ws, stream=None) -> None:
+    _check(lib().thc_prepare_range(C.byref(p), _ptr_array(grads), _ptr_array(ef), _ptr(range_M), _ptr(ws),
                                    _stream(stream)), "thc_prepare_range")
+
+
+def thc_compress_all(p: thc_params, rnd: int, grads, ef_inout, range_M, packed_out, ws, stream=None) -> None:
+    _check(lib().thc_compress_all(C.byref(p), rnd, _ptr_array(grads), _ptr_array(ef_inout), _ptr(range_M),
+                                  _ptr_array(packed_out), _ptr(ws), _stream(stream)), "thc_compress_all")
 
 
 def thc_compress(p: thc_params, worker_id: int, rnd: int, grad, ef_inout, range_M, packed_out, ws,

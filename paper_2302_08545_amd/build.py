@@ -35,23 +35,5 @@ def build(verbose: bool = False) -> str:
     return LIB_PATH
 
 
-def build_microbench(verbose: bool = False) -> str:
-    """The stand-alone access-pattern measurements (not part of the library) -> _build/access_patterns."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    out_dir = os.path.join(ROOT, "_build")
-    os.makedirs(out_dir, exist_ok=True)
-    out = os.path.join(out_dir, "access_patterns")
-    cmd = [hipcc, "-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           os.path.join(PKG_DIR, "csrc", "microbench", "access_patterns.hip"), "-o", out]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l))
-    return out
-
-
 if __name__ == "__main__":
     print(build(verbose=True))
-    if "--microbench" in sys.argv:
-        print(build_microbench(verbose=True))

@@ -34,6 +34,7 @@ int validate(const thc_params* p) {
   if (p->in_dtype != THC_DTYPE_F32 && p->in_dtype != THC_DTYPE_BF16) return THC_EINVAL;
   if (!(p->t_p > 0.f) || !std::isfinite(p->t_p)) return THC_EINVAL;
   if (p->stage_order != THC_ORDER_ASCENDING && p->stage_order != THC_ORDER_SPLIT) return THC_EINVAL;
+  if (p->group_log2 != 0 && (p->group_log2 < 10 || p->group_log2 > 40)) return THC_EINVAL;
   const uint32_t top = (1u << p->b) - 1;
   if (p->table[0] != 0 || p->table[top] != p->g) return THC_ETABLE;
   for (uint32_t z = 0; z < top; ++z)
@@ -162,9 +163,40 @@ TileMap lo_tilemap(const Plan& pl, uint64_t len) {
   return m.L ? m : pl.lo;
 }
 
+// ---- workspace layout --------------------------------------------------------------------------------------
+// [0, 256)        reserved
+// slot 0, slot 1  the half-rotated vectors of one group of blocks: slot_floats(p) binary32 values each
+// partials        n * (d >> min(L, 13)) binary64 partial sums of squares (one per 8192 coordinates, or per block)
+//
+// A group is a run of whole blocks of every vector in the call, sized so that the group's intermediate (all
+// vectors of the call together) is about 2^group_log2 coordinates: its writer and its reader then follow each other
+// closely enough for the intermediate to still sit in the 256 MB memory-side cache, and the workspace does not grow
+// with d.  Random streams are indexed by global coordinate, so the grouping never changes a result.
+constexpr size_t WS_HEADER = 256;
+constexpr uint32_t DEFAULT_GROUP_LOG2 = 25;
+
+uint64_t group_coords(const thc_params* p, uint32_t W) {
+  const uint64_t target = 1ull << (p->group_log2 ? p->group_log2 : DEFAULT_GROUP_LOG2);
+  uint64_t gc = target / W / p->block * p->block;
+  if (gc < p->block) gc = p->block;
+  if (gc > p->d) gc = p->d;
+  return gc;
+}
+
+uint64_t slot_floats(const thc_params* p) {
+  const uint64_t one = group_coords(p, 1), all = (uint64_t)p->n * group_coords(p, p->n);
+  return one > all ? one : all;
+}
+
 size_t partial_count(const thc_params* p, const Plan& pl) { return (size_t)p->n * (size_t)(p->d >> pl.L1); }
 
-size_t ws_x_bytes(const thc_params* p) { return (size_t)p->n * (size_t)p->d * sizeof(float); }
+float* ws_slot(void* ws, const thc_params* p, int which) {
+  return reinterpret_cast<float*>(static_cast<char*>(ws) + WS_HEADER) + (size_t)which * slot_floats(p);
+}
+
+double* ws_partials(void* ws, const thc_params* p) {
+  return reinterpret_cast<double*>(static_cast<char*>(ws) + WS_HEADER + 2 * slot_floats(p) * sizeof(float));
+}
 
 uint64_t tiles_of(uint64_t d) { return (d + TILE - 1) / TILE; }
 
@@ -214,53 +246,71 @@ void dispatch_0_9(int r, A&&... args) {
   }
 }
 
+// every launcher takes the number of vectors W of the launch: grid = (tiles, W)
 template <int R> struct LaunchMid {
-  static void run(const MidArgs& a, uint64_t tiles, hipStream_t s) { k_mid<R><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a); }
+  static void run(const MidArgs& a, uint64_t tiles, uint32_t W, hipStream_t s) {
+    k_mid<R><<<dim3((unsigned)tiles, W), dim3(NT), 0, s>>>(a);
+  }
 };
 template <int R> struct LaunchQuant {
-  static void run(const QuantArgs& a, bool cfold, uint64_t tiles, hipStream_t s) {
-    if (cfold && R >= 2) k_fwd_hi_quant<R, true><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a);
-    else k_fwd_hi_quant<R, false><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a);
+  static void run(const QuantArgs& a, bool cfold, uint64_t tiles, uint32_t W, hipStream_t s) {
+    if (cfold && R >= 2) k_fwd_hi_quant<R, true><<<dim3((unsigned)tiles, W), dim3(NT), 0, s>>>(a);
+    else k_fwd_hi_quant<R, false><<<dim3((unsigned)tiles, W), dim3(NT), 0, s>>>(a);
   }
 };
 template <int R> struct LaunchHiStore {
   static void run(const HiStoreArgs& a, uint64_t tiles, hipStream_t s) { k_fwd_hi_store<R><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a); }
 };
 template <int R> struct LaunchInvHi {
-  static void run(const InvHiArgs& a, uint64_t tiles, hipStream_t s) { k_inv_hi<R><<<dim3((unsigned)tiles), dim3(NT), 0, s>>>(a); }
+  static void run(const InvHiArgs& a, uint64_t tiles, uint32_t W, hipStream_t s) {
+    k_inv_hi<R><<<dim3((unsigned)tiles, W), dim3(NT), 0, s>>>(a);
+  }
 };
 
 template <int L1, bool BF16, bool EF>
-void launch_fwd_lo_k(const FwdLoArgs& a, bool split, uint64_t tiles, uint32_t n, hipStream_t s) {
+void launch_fwd_lo_k(const FwdLoArgs& a, bool split, bool norm_only, uint64_t tiles, uint32_t n, hipStream_t s) {
   const dim3 grid((unsigned)tiles, n);
   if constexpr (L1 == LOG_TILE) {
-    if (split) { k_fwd_lo<L1, BF16, EF, true><<<grid, dim3(NT), 0, s>>>(a); return; }
+    if (split) {
+      if (norm_only) k_fwd_lo<L1, BF16, EF, true, true><<<grid, dim3(NT), 0, s>>>(a);
+      else k_fwd_lo<L1, BF16, EF, true, false><<<grid, dim3(NT), 0, s>>>(a);
+      return;
+    }
   }
-  k_fwd_lo<L1, BF16, EF, false><<<grid, dim3(NT), 0, s>>>(a);
+  if (norm_only) k_fwd_lo<L1, BF16, EF, false, true><<<grid, dim3(NT), 0, s>>>(a);
+  else k_fwd_lo<L1, BF16, EF, false, false><<<grid, dim3(NT), 0, s>>>(a);
 }
 
 template <int L1>
-void launch_fwd_lo_t(const FwdLoArgs& a, bool bf16, bool ef, bool split, uint64_t tiles, uint32_t n, hipStream_t s) {
+void launch_fwd_lo_t(const FwdLoArgs& a, bool bf16, bool ef, bool split, bool norm_only, uint64_t tiles, uint32_t n,
+                     hipStream_t s) {
   if (bf16) {
-    if (ef) launch_fwd_lo_k<L1, true, true>(a, split, tiles, n, s);
-    else launch_fwd_lo_k<L1, true, false>(a, split, tiles, n, s);
+    if (ef) launch_fwd_lo_k<L1, true, true>(a, split, norm_only, tiles, n, s);
+    else launch_fwd_lo_k<L1, true, false>(a, split, norm_only, tiles, n, s);
   } else {
-    if (ef) launch_fwd_lo_k<L1, false, true>(a, split, tiles, n, s);
-    else launch_fwd_lo_k<L1, false, false>(a, split, tiles, n, s);
+    if (ef) launch_fwd_lo_k<L1, false, true>(a, split, norm_only, tiles, n, s);
+    else launch_fwd_lo_k<L1, false, false>(a, split, norm_only, tiles, n, s);
   }
 }
 
-void launch_fwd_lo(const Plan& pl, const FwdLoArgs& a, bool bf16, bool ef, uint64_t tiles, uint32_t n, hipStream_t s) {
+void launch_fwd_lo(const Plan& pl, const FwdLoArgs& a, bool bf16, bool ef, bool norm_only, uint64_t tiles, uint32_t n,
+                   hipStream_t s) {
   switch (pl.L1) {
-    case 10: launch_fwd_lo_t<10>(a, bf16, ef, false, tiles, n, s); break;
-    case 11: launch_fwd_lo_t<11>(a, bf16, ef, false, tiles, n, s); break;
-    case 12: launch_fwd_lo_t<12>(a, bf16, ef, false, tiles, n, s); break;
-    default: launch_fwd_lo_t<13>(a, bf16, ef, pl.split, tiles, n, s); break;
+    case 10: launch_fwd_lo_t<10>(a, bf16, ef, false, norm_only, tiles, n, s); break;
+    case 11: launch_fwd_lo_t<11>(a, bf16, ef, false, norm_only, tiles, n, s); break;
+    case 12: launch_fwd_lo_t<12>(a, bf16, ef, false, norm_only, tiles, n, s); break;
+    default: launch_fwd_lo_t<13>(a, bf16, ef, pl.split, norm_only, tiles, n, s); break;
   }
 }
 
-void launch_inv_lo(const Plan& pl, const InvLoArgs& a, uint64_t tiles, hipStream_t s) {
-  const dim3 grid((unsigned)tiles), blk(NT);
+void launch_range(const Plan& pl, const RangeArgs& r, hipStream_t s) {
+  const uint64_t K = r.d >> pl.L;
+  if (pl.L - pl.L1 <= 3) k_range_small<<<dim3((unsigned)((K + 255) / 256)), dim3(256), 0, s>>>(r);
+  else k_range<<<dim3((unsigned)K), dim3(RANGE_NT), 0, s>>>(r);
+}
+
+void launch_inv_lo(const Plan& pl, const InvLoArgs& a, uint64_t tiles, uint32_t W, hipStream_t s) {
+  const dim3 grid((unsigned)tiles, W), blk(NT);
   switch (pl.L1) {
     case 10: k_inv_lo<10, false><<<grid, blk, 0, s>>>(a); break;
     case 11: k_inv_lo<11, false><<<grid, blk, 0, s>>>(a); break;
@@ -272,65 +322,145 @@ void launch_inv_lo(const Plan& pl, const InvLoArgs& a, uint64_t tiles, hipStream
   }
 }
 
-// middle passes of one vector, in place
-void run_mids(const Plan& pl, float* x, uint64_t d, hipStream_t s) {
+// middle passes of W vectors of `d` coordinates each, in place
+void run_mids(const Plan& pl, float* x, uint64_t d, uint32_t W, hipStream_t s) {
   for (int m = 0; m < pl.nmid; ++m) {
     MidArgs a{x, d, pl.midmap[m]};
-    dispatch_0_7<LaunchMid>(pl.mid[m], a, tiles_of(d), s);
+    dispatch_0_7<LaunchMid>(pl.mid[m], a, tiles_of(d), W, s);
   }
 }
 
-// inverse transform of `len` coordinates that k_inv_lo is about to produce in `wsx`
-void run_inverse(const thc_params* p, const Plan& pl, InvLoArgs lo, float* wsx, InvHiArgs hi, uint64_t len,
+// inverse transform of W vectors of `len` coordinates that k_inv_lo is about to produce in `wsx`
+void run_inverse(const thc_params* p, const Plan& pl, InvLoArgs lo, float* wsx, InvHiArgs hi, uint64_t len, uint32_t W,
                  hipStream_t s) {
   lo.tm = lo_tilemap(pl, len);
   lo.ws_x = wsx;
   lo.d = len;
-  launch_inv_lo(pl, lo, tiles_of(len), s);
-  run_mids(pl, wsx, len, s);
+  launch_inv_lo(pl, lo, tiles_of(len), W, s);
+  run_mids(pl, wsx, len, W, s);
   hi.x = wsx;
   hi.d = len;
   hi.tm = pl.hi;
   hi.c = (float)(1.0 / std::sqrt((double)p->block));
-  dispatch_0_9<LaunchInvHi>(pl.R, hi, tiles_of(len), s);
+  dispatch_0_9<LaunchInvHi>(pl.R, hi, tiles_of(len), W, s);
 }
 
-// Kernels that hand a vector to each other through the workspace (inverse lo -> hi, middle passes, the error-feedback
-// chain) work on pieces of this many coordinates, one after the other, and the intermediate of every piece after the
-// first lands on the same 128 MB of the workspace: it then stays in the 256 MB memory-side cache between its
-// writer and its reader instead of travelling to HBM and back.  Whole blocks; random streams are indexed by
-// global coordinate (the kernels' j0).
-// The environment variable THC_PIECE_LOG2 (10..40) overrides the default piece of 2^25 coordinates: results do not
-// depend on it, only the speed (and tests use it to cut small vectors into several pieces).
-uint64_t piece_coords(const thc_params* p) {
-  uint64_t target = 1ull << 25;
-  if (const char* e = std::getenv("THC_PIECE_LOG2")) {
-    const long v = std::strtol(e, nullptr, 10);
-    if (v >= 10 && v <= 40) target = 1ull << v;
+// Worker side of one round (Alg. 3) for W co-resident vectors, group by group:
+//   first pass (x = grad + e, diagonal, 13 stages; with `range_out` also the norms) -> [range] -> middle passes ->
+//   last pass + quantizer -> [error feedback: indices -> inverse first pass -> middle passes -> inverse last pass].
+// Every kernel of a group covers all W vectors (grid.y), so a group costs the same number of launches for any W.
+struct Forward {
+  const thc_params* p;
+  uint64_t round;
+  uint32_t W;                  // vectors in the call
+  uint32_t worker0;            // worker id of vector 0 (vector i is worker worker0 + i)
+  const void* const* grads;    // W device pointers
+  float* const* efs;           // W device pointers, or null: no error feedback
+  float* range_out;            // not null: M_k from the W vectors' norms, written here and used
+  const float* range_in;       // used when range_out is null
+  uint8_t* const* packed;      // W device pointers
+  void* ws;
+  hipStream_t s;
+};
+
+void run_forward(const Forward& f) {
+  const thc_params* p = f.p;
+  const Plan pl = make_plan(p->block, p->stage_order);
+  const bool bf16 = p->in_dtype == THC_DTYPE_BF16;
+  const size_t in_size = bf16 ? 2 : 4;
+  const uint64_t gc = group_coords(p, f.W);
+  float* const slot = ws_slot(f.ws, p, 0);
+  double* const partials = ws_partials(f.ws, p);
+  const float* const range = f.range_out ? f.range_out : f.range_in;
+
+  QuantArgs q{};
+  q.tm = pl.hi;
+  q.L = (uint32_t)pl.L;
+  q.b = p->b;
+  q.g = p->g;
+  q.round = (uint32_t)f.round;
+  q.worker = f.worker0;
+  q.k0 = (uint32_t)p->seed;
+  q.k1 = (uint32_t)(p->seed >> 32);
+  q.c = (float)(1.0 / std::sqrt((double)p->block));
+  fill_lut(p, q.lut);   // per grid cell k: the largest index z0 with T[z0] <= k, its value and the gap to the next
+  InvLoArgs ilo{};
+  InvHiArgs ihi{};
+  if (f.efs) {
+    ilo.L = (uint32_t)pl.L;
+    ilo.src_bits = p->b;
+    ilo.use_table = 1;
+    ilo.divisor = p->g;
+    std::memcpy(ilo.table, p->table, 256);
+    ihi.round = (uint32_t)f.round;
+    ihi.k0 = q.k0;
+    ihi.k1 = q.k1;
+    ihi.mode = 1;
+    ihi.bf16 = bf16;
   }
-  return p->block > target ? p->block : target;
+  for (uint64_t x0 = 0; x0 < p->d; x0 += gc) {
+    const uint64_t len = p->d - x0 < gc ? p->d - x0 : gc;
+    const uint64_t tiles = tiles_of(len);
+    FwdLoArgs a{};
+    for (uint32_t i = 0; i < f.W; ++i) {
+      a.grads.p[i] = static_cast<const char*>(f.grads[i]) + x0 * in_size;
+      if (f.efs) a.efs.p[i] = f.efs[i] + x0;
+      q.packed.p[i] = f.packed[i] + x0 / 8 * p->b;
+      if (f.efs) {
+        ilo.src.p[i] = q.packed.p[i];
+        ihi.out.p[i] = f.efs[i] + x0;
+        ihi.grad.p[i] = a.grads.p[i];
+      }
+    }
+    a.ws_x = slot;
+    a.partials = f.range_out ? partials + (x0 >> pl.L1) : nullptr;
+    a.pstride = p->d >> pl.L1;
+    a.d = len;
+    a.j0 = base_coord(p) + x0;
+    a.round = (uint32_t)f.round;
+    a.k0 = q.k0;
+    a.k1 = q.k1;
+    a.tm = lo_tilemap(pl, len);
+    launch_fwd_lo(pl, a, bf16, f.efs != nullptr, false, tiles, f.W, f.s);
+    if (f.range_out) {
+      RangeArgs r{a.partials, f.range_out + x0 / p->block, a.pstride, len, f.W, (uint32_t)pl.L, (uint32_t)pl.L1, p->t_p};
+      launch_range(pl, r, f.s);
+    }
+    run_mids(pl, slot, len, f.W, f.s);
+    q.x = slot;
+    q.range_M = range + x0 / p->block;
+    q.d = len;
+    q.j0 = a.j0;
+    dispatch_0_9<LaunchQuant>(pl.R, q, (pl.L & 1) == 0, tiles, f.W, f.s);
+    if (f.efs) {
+      // e <- (grad + e) - RHT^-1(X_i): the group's slot is free again and takes the inverse's intermediate
+      ilo.range_M = q.range_M;
+      ihi.j0 = a.j0;
+      run_inverse(p, pl, ilo, slot, ihi, len, f.W, f.s);
+    }
+  }
 }
 
 const char* const kNames[] = {"THC_OK", "THC_EINVAL", "THC_ETABLE", "THC_EOVERFLOW", "THC_EUNSUPPORTED", "THC_ELAUNCH"};
-
 
 }  // namespace
 
 extern "C" {
 
-int thc_version(void) { return 100; }
+int thc_version(void) { return 200; }
 
 const char* thc_strerror(int status) {
   const int i = -status;
   return (i >= 0 && i <= 5) ? kNames[i] : "THC_E?";
 }
 
-int thc_workspace_bytes(const thc_params* p, size_t* bytes_out) {
+int thc_workspace_bytes(const thc_params* p, int ef_enabled, size_t* bytes_out) {
   const int rc = validate(p);
   if (rc) return rc;
   if (!bytes_out) return THC_EINVAL;
+  (void)ef_enabled;   // the error-feedback update reuses the slot its group has just been quantized from
   const Plan pl = make_plan(p->block, p->stage_order);
-  *bytes_out = ws_x_bytes(p) + partial_count(p, pl) * (sizeof(double) + 2 * sizeof(float)) + 256;
+  *bytes_out = WS_HEADER + 2 * slot_floats(p) * sizeof(float) + partial_count(p, pl) * sizeof(double) + 256;
   return THC_OK;
 }
 
@@ -355,44 +485,50 @@ int thc_describe_plan(const thc_params* p, uint32_t* out, size_t cap_records) {
   };
   int first[16];
   for (int i = 0; i < pl.L1; ++i) first[i] = (pl.split && i >= 10) ? i + 3 : i;
-  put(0, pl.split ? 3u : 0u, first, pl.L1, lo_tilemap(pl, p->d));
+  put(0, pl.split ? 3u : 0u, first, pl.L1, lo_tilemap(pl, group_coords(p, p->n)));
   for (int m = 0; m < pl.nmid; ++m) put(1 + m, 1u, pl.bits[m], pl.mid[m], pl.midmap[m]);
   put(npass - 1, 2u, pl.bits[pl.nmid], pl.R, pl.hi);
   return npass;
 }
 
-int thc_prepare_range(const thc_params* p, uint64_t round, const void* const* grads, const float* const* ef,
-                      float* range_M, void* ws, void* stream) {
-  const int rc = validate(p);
-  if (rc) return rc;
-  if (!grads || !ws || !aligned16(ws) || round >> 32) return THC_EINVAL;
-  if (range_M && (reinterpret_cast<uintptr_t>(range_M) & 3u)) return THC_EINVAL;
-  FwdLoArgs a{};
+namespace {
+
+int check_vectors(const thc_params* p, const void* const* grads, const float* const* ef) {
+  if (!grads) return THC_EINVAL;
   for (uint32_t i = 0; i < p->n; ++i) {
     if (!grads[i] || !aligned16(grads[i])) return THC_EINVAL;
-    a.grads.p[i] = grads[i];
-    if (ef) {
-      if (!ef[i] || !aligned16(ef[i])) return THC_EINVAL;
-      a.efs.p[i] = ef[i];
-    }
+    if (ef && (!ef[i] || !aligned16(ef[i]))) return THC_EINVAL;
   }
+  return THC_OK;
+}
+
+}  // namespace
+
+int thc_prepare_range(const thc_params* p, const void* const* grads, const float* const* ef, float* range_M, void* ws,
+                      void* stream) {
+  const int rc = validate(p);
+  if (rc) return rc;
+  if (!ws || !aligned16(ws) || !range_M || (reinterpret_cast<uintptr_t>(range_M) & 3u)) return THC_EINVAL;
+  const int rv = check_vectors(p, grads, ef);
+  if (rv) return rv;
   const Plan pl = make_plan(p->block, p->stage_order);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  a.ws_x = static_cast<float*>(ws);
-  a.partials = reinterpret_cast<double*>(static_cast<char*>(ws) + ws_x_bytes(p));
-  a.d = p->d;
-  a.j0 = base_coord(p);
-  a.round = (uint32_t)round;
-  a.k0 = (uint32_t)p->seed;
-  a.k1 = (uint32_t)(p->seed >> 32);
-  a.tm = lo_tilemap(pl, p->d);
-  launch_fwd_lo(pl, a, p->in_dtype == THC_DTYPE_BF16, ef != nullptr, tiles_of(p->d), p->n, s);
-  if (range_M) {
-    RangeArgs r{a.partials, range_M, p->d, p->n, (uint32_t)pl.L, (uint32_t)pl.L1, p->t_p};
-    const uint64_t K = p->d / p->block;
-    if (pl.L - pl.L1 <= 3) k_range_small<<<dim3((unsigned)((K + 255) / 256)), dim3(256), 0, s>>>(r);
-    else k_range<<<dim3((unsigned)K), dim3(RANGE_NT), 0, s>>>(r);
+  // The same partial sums, in the same order, as the first pass of thc_compress_all takes them group by group: both
+  // give the same M bit for bit.
+  const bool bf16 = p->in_dtype == THC_DTYPE_BF16;
+  double* const partials = ws_partials(ws, p);
+  FwdLoArgs a{};
+  for (uint32_t i = 0; i < p->n; ++i) {
+    a.grads.p[i] = grads[i];
+    if (ef) a.efs.p[i] = ef[i];
   }
+  a.partials = partials;
+  a.pstride = p->d >> pl.L1;
+  a.d = p->d;
+  a.tm = lo_tilemap(pl, p->d);
+  launch_fwd_lo(pl, a, bf16, ef != nullptr, true, tiles_of(p->d), p->n, s);
+  RangeArgs r{partials, range_M, p->d >> pl.L1, p->d, p->n, (uint32_t)pl.L, (uint32_t)pl.L1, p->t_p};
+  launch_range(pl, r, s);
   return check_launch();
 }
 
@@ -400,63 +536,27 @@ int thc_compress(const thc_params* p, uint32_t worker_id, uint64_t round, const 
                  const float* range_M, uint8_t* packed_out, void* ws, void* stream) {
   const int rc = validate(p);
   if (rc) return rc;
-  if (worker_id >= p->n || round >> 32 || !range_M || !packed_out || !ws) return THC_EINVAL;
-  if (!aligned16(packed_out) || !aligned16(ws)) return THC_EINVAL;
-  if (ef_inout && (!grad || !aligned16(grad) || !aligned16(ef_inout))) return THC_EINVAL;
-  const Plan pl = make_plan(p->block, p->stage_order);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  float* wsx = static_cast<float*>(ws) + (size_t)worker_id * p->d;
+  if (worker_id >= p->n || round >> 32 || !range_M || !packed_out || !ws || !grad) return THC_EINVAL;
+  if (!aligned16(packed_out) || !aligned16(ws) || !aligned16(grad)) return THC_EINVAL;
+  if (ef_inout && !aligned16(ef_inout)) return THC_EINVAL;
+  Forward f{p, round, 1, worker_id, &grad, ef_inout ? &ef_inout : nullptr, nullptr, range_M, &packed_out, ws,
+            static_cast<hipStream_t>(stream)};
+  run_forward(f);
+  return check_launch();
+}
 
-  QuantArgs q{};
-  q.tm = pl.hi;
-  q.L = (uint32_t)pl.L;
-  q.b = p->b;
-  q.g = p->g;
-  q.round = (uint32_t)round;
-  q.worker = worker_id;
-  q.k0 = (uint32_t)p->seed;
-  q.k1 = (uint32_t)(p->seed >> 32);
-  q.c = (float)(1.0 / std::sqrt((double)p->block));
-  fill_lut(p, q.lut);   // per grid cell k: the largest index z0 with T[z0] <= k, its value and the gap to the next
-  InvLoArgs lo{};
-  InvHiArgs hi{};
-  if (ef_inout) {
-    lo.L = (uint32_t)pl.L;
-    lo.src_bits = p->b;
-    lo.use_table = 1;
-    lo.divisor = p->g;
-    std::memcpy(lo.table, p->table, 256);
-    hi.round = (uint32_t)round;
-    hi.k0 = q.k0;
-    hi.k1 = q.k1;
-    hi.mode = 1;
-    hi.bf16 = p->in_dtype == THC_DTYPE_BF16;
-  }
-  // Pieces pay off (measured) once three or more kernels follow each other on the same data, as in the
-  // error-feedback chain; every extra launch costs about 7 us, which a chain of two does not earn back.
-  const uint64_t piece = ef_inout ? piece_coords(p) : p->d;
-  const size_t in_size = p->in_dtype == THC_DTYPE_BF16 ? 2 : 4;
-  for (uint64_t j0 = 0; j0 < p->d; j0 += piece) {
-    const uint64_t len = p->d - j0 < piece ? p->d - j0 : piece;
-    const float* rM = range_M + j0 / p->block;
-    uint8_t* pk = packed_out + j0 / 8 * p->b;
-    run_mids(pl, wsx + j0, len, s);
-    q.x = wsx + j0;
-    q.range_M = rM;
-    q.packed = pk;
-    q.d = len;
-    q.j0 = base_coord(p) + j0;
-    dispatch_0_9<LaunchQuant>(pl.R, q, (pl.L & 1) == 0, tiles_of(len), s);
-    if (ef_inout) {
-      lo.src = pk;
-      lo.range_M = rM;
-      hi.out = ef_inout + j0;
-      hi.grad = static_cast<const char*>(grad) + j0 * in_size;
-      hi.j0 = base_coord(p) + j0;
-      // the first piece's own part of the workspace is free once its quantizer has run, and serves all later pieces
-      run_inverse(p, pl, lo, wsx, hi, len, s);
-    }
-  }
+int thc_compress_all(const thc_params* p, uint64_t round, const void* const* grads, float* const* ef_inout,
+                     float* range_M, uint8_t* const* packed_out, void* ws, void* stream) {
+  const int rc = validate(p);
+  if (rc) return rc;
+  if (round >> 32 || !ws || !aligned16(ws) || !range_M || (reinterpret_cast<uintptr_t>(range_M) & 3u) || !packed_out)
+    return THC_EINVAL;
+  const int rv = check_vectors(p, grads, ef_inout);
+  if (rv) return rv;
+  for (uint32_t i = 0; i < p->n; ++i)
+    if (!packed_out[i] || !aligned16(packed_out[i])) return THC_EINVAL;
+  Forward f{p, round, p->n, 0, grads, ef_inout, range_M, nullptr, packed_out, ws, static_cast<hipStream_t>(stream)};
+  run_forward(f);
   return check_launch();
 }
 
@@ -523,7 +623,7 @@ int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const f
   if (!aligned16(agg) || !aligned16(out) || !aligned16(ws)) return THC_EINVAL;
   const Plan pl = make_plan(p->block, p->stage_order);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  float* wsx = static_cast<float*>(ws);
+  float* const slot = ws_slot(ws, p, 0);
   InvLoArgs lo{};
   lo.L = (uint32_t)pl.L;
   lo.src_bits = p->agg_bits;
@@ -534,14 +634,14 @@ int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const f
   hi.k0 = (uint32_t)p->seed;
   hi.k1 = (uint32_t)(p->seed >> 32);
   hi.mode = 0;
-  const uint64_t piece = pl.nmid > 0 ? piece_coords(p) : p->d;   // lo -> hi alone does not earn the launches back
-  for (uint64_t j0 = 0; j0 < p->d; j0 += piece) {
-    const uint64_t len = p->d - j0 < piece ? p->d - j0 : piece;
-    lo.src = static_cast<const uint8_t*>(agg) + j0 / 8 * p->agg_bits;
-    lo.range_M = range_M + j0 / p->block;
-    hi.out = out + j0;
-    hi.j0 = base_coord(p) + j0;
-    run_inverse(p, pl, lo, wsx, hi, len, s);
+  const uint64_t gc = group_coords(p, 1);
+  for (uint64_t x0 = 0; x0 < p->d; x0 += gc) {
+    const uint64_t len = p->d - x0 < gc ? p->d - x0 : gc;
+    lo.src.p[0] = static_cast<const uint8_t*>(agg) + x0 / 8 * p->agg_bits;
+    lo.range_M = range_M + x0 / p->block;
+    hi.out.p[0] = out + x0;
+    hi.j0 = base_coord(p) + x0;
+    run_inverse(p, pl, lo, slot, hi, len, 1, s);
   }
   return check_launch();
 }
@@ -557,11 +657,24 @@ int validate_uniform(const thc_params* p) {
   return THC_OK;
 }
 
-float* pmin_of(const thc_params* p, const Plan& pl, void* ws) {
-  return reinterpret_cast<float*>(static_cast<char*>(ws) + ws_x_bytes(p) + partial_count(p, pl) * sizeof(double));
+// Workspace of the uniform entry points: with rotation the fully rotated vectors of all n workers (n*d binary32
+// values, kept from thc_uniform_prepare_range to thc_uniform_compress), then per-tile minima and maxima.
+size_t uni_x_bytes(const thc_params* p, int rotate) { return rotate ? (size_t)p->n * (size_t)p->d * sizeof(float) : 0; }
+
+float* pmin_of(const thc_params* p, int rotate, void* ws) {
+  return reinterpret_cast<float*>(static_cast<char*>(ws) + uni_x_bytes(p, rotate));
 }
 
 }  // namespace
+
+int thc_uniform_workspace_bytes(const thc_params* p, int rotate, size_t* bytes_out) {
+  const int rc = validate_uniform(p);
+  if (rc) return rc;
+  if (!bytes_out) return THC_EINVAL;
+  const Plan pl = make_plan(p->block, p->stage_order);
+  *bytes_out = uni_x_bytes(p, rotate) + partial_count(p, pl) * 2 * sizeof(float) + 256;
+  return THC_OK;
+}
 
 int thc_uniform_prepare_range(const thc_params* p, uint64_t round, const void* const* grads, const float* const* ef,
                               int rotate, float* range_m, float* range_M, void* ws, void* stream) {
@@ -574,17 +687,28 @@ int thc_uniform_prepare_range(const thc_params* p, uint64_t round, const void* c
   }
   const Plan pl = make_plan(p->block, p->stage_order);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  float* pmin = pmin_of(p, pl, ws);
+  float* pmin = pmin_of(p, rotate, ws);
   float* pmax = pmin + partial_count(p, pl);
   const size_t per_worker = (size_t)(p->d >> pl.L1);
   const bool bf16 = p->in_dtype == THC_DTYPE_BF16;
   if (rotate) {
     // full forward RHT of every worker, kept in the workspace
-    const int r0 = thc_prepare_range(p, round, grads, ef, nullptr, ws, stream);
-    if (r0) return r0;
+    FwdLoArgs a{};
+    for (uint32_t i = 0; i < p->n; ++i) {
+      a.grads.p[i] = grads[i];
+      if (ef) a.efs.p[i] = ef[i];
+    }
+    a.ws_x = static_cast<float*>(ws);
+    a.d = p->d;
+    a.j0 = base_coord(p);
+    a.round = (uint32_t)round;
+    a.k0 = (uint32_t)p->seed;
+    a.k1 = (uint32_t)(p->seed >> 32);
+    a.tm = lo_tilemap(pl, p->d);
+    launch_fwd_lo(pl, a, bf16, ef != nullptr, false, tiles_of(p->d), p->n, s);
+    run_mids(pl, static_cast<float*>(ws), p->d, p->n, s);
     for (uint32_t i = 0; i < p->n; ++i) {
       float* wsx = static_cast<float*>(ws) + (size_t)i * p->d;
-      run_mids(pl, wsx, p->d, s);
       HiStoreArgs h{wsx, pmin + i * per_worker, pmax + i * per_worker, p->d, pl.hi, (uint32_t)pl.L,
                     (float)(1.0 / std::sqrt((double)p->block))};
       dispatch_0_9<LaunchHiStore>(pl.R, h, tiles_of(p->d), s);
@@ -644,7 +768,7 @@ int thc_uniform_compress(const thc_params* p, uint32_t worker_id, uint64_t round
   if (rotate && ef_inout) {
     // e <- (grad + e) - RHT^-1(X_i): rebuild X_i from the indices, inverse transform, subtract
     InvLoArgs lo{};
-    lo.src = packed_out;
+    lo.src.p[0] = packed_out;
     lo.range_M = range_M;
     lo.range_m = range_m;
     lo.ws_x = wsx;
@@ -655,15 +779,15 @@ int thc_uniform_compress(const thc_params* p, uint32_t worker_id, uint64_t round
     lo.divisor = p->g;
     std::memcpy(lo.table, p->table, 256);
     InvHiArgs hi{};
-    hi.out = ef_inout;
-    hi.grad = grad;
+    hi.out.p[0] = ef_inout;
+    hi.grad.p[0] = grad;
     hi.round = (uint32_t)round;
     hi.k0 = q.k0;
     hi.k1 = q.k1;
     hi.mode = 1;
     hi.bf16 = p->in_dtype == THC_DTYPE_BF16;
     hi.j0 = base_coord(p);
-    run_inverse(p, pl, lo, wsx, hi, p->d, s);
+    run_inverse(p, pl, lo, wsx, hi, p->d, 1, s);
   }
   return check_launch();
 }
@@ -684,7 +808,7 @@ int thc_uniform_decompress(const thc_params* p, uint64_t round, const void* agg,
   }
   float* wsx = static_cast<float*>(ws);
   InvLoArgs lo{};
-  lo.src = agg;
+  lo.src.p[0] = agg;
   lo.range_M = range_M;
   lo.range_m = range_m;
   lo.ws_x = wsx;
@@ -694,13 +818,13 @@ int thc_uniform_decompress(const thc_params* p, uint64_t round, const void* agg,
   lo.use_table = 0;
   lo.divisor = p->g * p->n;
   InvHiArgs hi{};
-  hi.out = out;
+  hi.out.p[0] = out;
   hi.round = (uint32_t)round;
   hi.k0 = (uint32_t)p->seed;
   hi.k1 = (uint32_t)(p->seed >> 32);
   hi.mode = 0;
   hi.j0 = base_coord(p);
-  run_inverse(p, pl, lo, wsx, hi, p->d, s);
+  run_inverse(p, pl, lo, wsx, hi, p->d, 1, s);
   return check_launch();
 }
 

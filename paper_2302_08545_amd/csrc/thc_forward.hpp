@@ -14,7 +14,8 @@ struct FwdLoArgs {
   PtrArr grads;
   PtrArr efs;          // unused without error feedback
   float* ws_x;         // n * d floats
-  double* partials;    // n * (d >> min(L, 13)) doubles
+  double* partials;    // per worker `pstride` doubles, one per min(B, 8192) coordinates; or null: no norms wanted
+  uint64_t pstride;
   uint64_t d;
   uint64_t j0;         // global coordinate of the vectors' first element (a multiple of B): indexes the diagonal
   uint32_t round, k0, k1;
@@ -41,7 +42,8 @@ __device__ __forceinline__ float4 load_grad4(const void* g, uint64_t j) {
 
 // One workgroup per tile (grid = (tiles, n workers)): measured on MI355X this streams faster than a
 // persistent grid with software prefetch, the hardware dispatcher keeps four workgroups per CU in flight.
-template <int L1, bool BF16, bool EF, bool XO>
+// NORM_ONLY: stop after the partial sums of squares (the norm exchange of Alg. 3 on its own): same sums, same order.
+template <int L1, bool BF16, bool EF, bool XO, bool NORM_ONLY = false>
 __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
   static_assert(!XO || L1 == LOG_TILE, "the row-split tile needs blocks of at least 2^16");
   // Vectors are multiples of B, so only blocks shorter than a tile can leave the last tile partial.
@@ -71,7 +73,7 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
     }
   }
 
-  if (t < 64) {   // the tile's 8192 diagonal entries: 64 Philox calls of 128 bits
+  if (!NORM_ONLY && t < 64) {   // the tile's 8192 diagonal entries: 64 Philox calls of 128 bits
     const uint64_t q = (a.j0 + off + lo_map<XO>(128u * t)) >> 7;
     const uint4 r = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, SIGN_STREAM, a.k0, a.k1);
     *reinterpret_cast<uint4*>(&sgn[4 * t]) = r;
@@ -121,8 +123,9 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
     // the row-split tile is not contiguous: its number stands in (the same block either way); a contiguous tile
     // is numbered by where it lies
     const uint64_t pidx = XO ? (uint64_t)blockIdx.x : (off >> L1) + t;
-    if (pidx < (a.d >> L1)) a.partials[(uint64_t)worker * (a.d >> L1) + pidx] = s;
+    if (a.partials && pidx < (a.d >> L1)) a.partials[(uint64_t)worker * a.pstride + pidx] = s;
   }
+  if constexpr (NORM_ONLY) return;
 
   // diagonal, strides 1 and 2, then into LDS
 #pragma unroll
@@ -148,8 +151,9 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
 // Range (Sec. 5.3; Alg. 3: M = (t_p / sqrt(d)) * max_i ||x_i||, per block).
 // ---------------------------------------------------------------------------------------------
 struct RangeArgs {
-  const double* partials;   // n * (d >> L1)
+  const double* partials;   // per worker `pstride` doubles
   float* range_M;           // K
+  uint64_t pstride;
   uint64_t d;
   uint32_t n, L, L1;
   float t_p;
@@ -167,7 +171,7 @@ __global__ __launch_bounds__(256) void k_range_small(const RangeArgs a) {
   const uint64_t k = (uint64_t)blockIdx.x * 256 + threadIdx.x;
   if (k >= (a.d >> a.L)) return;
   const uint32_t ppb = 1u << (a.L - a.L1);
-  const uint64_t per_worker = a.d >> a.L1;
+  const uint64_t per_worker = a.pstride;
   double smax = 0.0;
   for (uint32_t i = 0; i < a.n; ++i) {
     const double* p = a.partials + (uint64_t)i * per_worker + k * ppb;
@@ -186,7 +190,7 @@ __global__ __launch_bounds__(RANGE_NT) void k_range(const RangeArgs a) {
   const uint64_t k = blockIdx.x;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const uint32_t ppb = 1u << (a.L - a.L1);           // partials per block
-  const uint64_t per_worker = a.d >> a.L1;
+  const uint64_t per_worker = a.pstride;
   for (uint32_t i = 0; i < a.n; ++i) {
     const double* p = a.partials + (uint64_t)i * per_worker + k * ppb;
     double s = 0.0;
@@ -328,16 +332,17 @@ __device__ __forceinline__ void hi_load_to_lds(const float* src, const HiGeom<R>
 // "mid" pass: R more bits, in place.
 // ---------------------------------------------------------------------------------------------
 struct MidArgs {
-  float* x;   // d floats (one worker's half-rotated vector)
+  float* x;   // d floats per worker of the launch (grid.y = worker): half-rotated vectors
   uint64_t d;
   TileMap tm;
 };
 
 template <int R>
-__global__ __launch_bounds__(NT) void k_mid(const MidArgs a) {
+__global__ __launch_bounds__(NT) void k_mid(MidArgs a) {
   __shared__ __align__(16) float lds[TILE];
   const int t = threadIdx.x;
   const HiGeom<R> g(blockIdx.x, a.tm);
+  a.x += (uint64_t)blockIdx.y * a.d;
   if constexpr (R >= 2) {
     hi_front<R>(a.x, g, lds, t);
     int idx[2];
@@ -374,16 +379,16 @@ __global__ __launch_bounds__(NT) void k_mid(const MidArgs a) {
 // so every rounding stays where it was.
 // ---------------------------------------------------------------------------------------------
 struct QuantArgs {
-  const float* x;          // one worker's half-rotated vector, d floats
+  const float* x;          // half-rotated vectors, d floats per worker of the launch (grid.y = worker)
   const float* range_M;    // K floats
   const float* range_m;    // K floats, or null: m = -M
-  uint8_t* packed;         // d*b/8 bytes
+  PtrArr packed;           // per worker of the launch: d*b/8 bytes, written
   uint64_t d;
   uint64_t j0;             // global coordinate of x[0] (a multiple of B): the random streams are indexed globally
   TileMap tm;
   uint32_t L;              // log2 B
   uint32_t b, g;
-  uint32_t round, worker, k0, k1;
+  uint32_t round, worker, k0, k1;   // worker: id of the launch's first worker (selects the rounding stream)
   float c;                 // 1/sqrt(B)
   uint32_t lut[256];       // per grid cell k: lo | wd << 8 | z0 << 16
 };
@@ -392,18 +397,22 @@ struct QuantScalars {
   float M, lo, sc16, c;  // range [lo, M]; for even log2 B they and sc16 are pre-scaled by c, and c is unused
 };
 
-template <bool CFOLD>
+// WIDE = false: the fast form, on the grid position scaled by 2^16 (sc16 = scale * 2^16, range optionally folded
+// with 1/sqrt(B)).  WIDE = true: ranges so narrow that scale * 2^16 would overflow binary32: the operations exactly
+// as listed above (sc16 then holds the plain scale, the range is not folded), and the comparison scales t instead.
+// Both forms take the same decisions: multiplying by a power of two commutes with every rounding involved.
+template <bool CFOLD, bool WIDE = false>
 __device__ __forceinline__ void quantize8(const float (&hv)[8], const uint4 rnd, const QuantScalars s,
                                           const uint4* lut, uint32_t (&z)[8]) {
   const uint32_t rw[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const float v = CFOLD ? hv[e] : hv[e] * s.c;
+    const float v = (CFOLD && !WIDE) ? hv[e] : hv[e] * s.c;
     const float xc = __builtin_amdgcn_fmed3f(v, s.lo, s.M);
-    const float y16 = (xc - s.lo) * s.sc16;
+    const float y16 = (xc - s.lo) * s.sc16;          // WIDE: the grid position y itself
     const uint32_t ki = (uint32_t)y16;
-    const uint4 ent = lut[(ki >> 16) & 255u];
-    const float t16 = y16 - __uint_as_float(ent.x);
+    const uint4 ent = lut[(WIDE ? ki : ki >> 16) & 255u];
+    const float t16 = WIDE ? (y16 - __uint_as_float(ent.x) * 0x1p-16f) * 65536.0f : y16 - __uint_as_float(ent.x);
     const float hf = (float)((e & 1) ? (rw[e >> 1] >> 16) : (rw[e >> 1] & 0xFFFFu));
     const float prod = __builtin_fmaf(hf, __uint_as_float(ent.y), __uint_as_float(ent.z));
     z[e] = ent.w + (prod < t16 ? 1u : 0u);
@@ -446,12 +455,24 @@ __device__ __forceinline__ void build_quant_lut(const QuantArgs& a, uint4* lut, 
   if (t < 256) lut[t] = quant_lut_entry(a.lut[t]);
 }
 
-// g / (M - m) * 2^16: the width in binary64, the quotient rounded once to binary32.  An empty range gives 0 (every
-// index 0); widths below 2^-100 count as empty: there the scale, its 2^16 multiple and the folded 1/sqrt(B) would
-// leave binary32's normal range.
-__device__ __forceinline__ float scale16_of(float M, float m, uint32_t g) {
-  const double W = (double)M - (double)m;
-  return W >= 0x1p-100 ? (float)((double)g / W) * 65536.0f : 0.f;
+// scale = g / (M - m): the width in binary64, the quotient rounded once to binary32.  Where that is not a finite
+// number (M = m, or a width so small that the quotient overflows binary32) the range is empty: scale 0, every index 0.
+__device__ __forceinline__ float scale_of(float M, float m, uint32_t g) {
+  const float sc = (float)((double)g / ((double)M - (double)m));
+  return sc <= 3.4028234663852886e38f ? sc : 0.f;     // also false for NaN
+}
+
+// scale * 2^16 (and the fold with 1/sqrt(B)) stay finite below this
+constexpr float WIDE_SCALE = 0x1p110f;
+
+// Per-block constants of the quantizer: the fast form whenever scale * 2^16 is representable.
+__device__ __forceinline__ QuantScalars quant_scalars(float M, float m, uint32_t g, float c, bool cfold, bool& wide) {
+  const float sc = scale_of(M, m, g);
+  wide = sc >= WIDE_SCALE;
+  if (wide) return QuantScalars{M, m, sc, c};
+  const float sc16 = sc * 65536.0f;
+  if (cfold) return QuantScalars{M * (1.0f / c), m * (1.0f / c), sc16 * c, c};
+  return QuantScalars{M, m, sc16, c};
 }
 
 __device__ __forceinline__ float lower_of(const float* range_m, uint64_t blk, float M) {
@@ -462,38 +483,44 @@ template <int R, bool CFOLD>
 __global__ __launch_bounds__(NT, 8) void k_fwd_hi_quant(const QuantArgs a) {
   __shared__ __align__(16) float lds[TILE];
   __shared__ uint4 lut[256];
-  __shared__ float sM[8], sLo[8], sScale[8];
+  __shared__ QuantScalars sQ[8];
+  __shared__ int sWide[8];
 
   const int t = threadIdx.x;
+  const uint32_t wk = blockIdx.y;                         // worker of the launch
+  const float* const xw = a.x + (uint64_t)wk * a.d;
+  uint8_t* const packed = static_cast<uint8_t*>(const_cast<void*>(a.packed.p[wk]));
+  const uint32_t stream = a.worker + wk;
 
   if constexpr (R >= 2) {
     const HiGeom<R> g(blockIdx.x, a.tm);
     float4 x[4];
-    hi_issue_loads<R>(a.x, g, t, x);            // tile loads first: everything below overlaps their latency
+    hi_issue_loads<R>(xw, g, t, x);             // tile loads first: everything below overlaps their latency
     build_quant_lut(a, lut, t);
     if (t == 0) {                               // the whole tile lies in one block
       const uint64_t blk = g.base >> a.L;
       const float M = a.range_M[blk], m = lower_of(a.range_m, blk, M);
-      const float sc = scale16_of(M, m, a.g);
-      sM[0] = CFOLD ? M * (1.0f / a.c) : M;
-      sLo[0] = CFOLD ? m * (1.0f / a.c) : m;
-      sScale[0] = CFOLD ? sc * a.c : sc;
+      bool wide;
+      sQ[0] = quant_scalars(M, m, a.g, a.c, CFOLD, wide);
+      sWide[0] = wide;
     }
     hi_r0_to_lds<R>(x, lds, t);
     hi_round1<R>(lds, t);
     int idx[2];
     float v[2][8];
     hi_back<R>(lds, t, idx, v);
-    const QuantScalars s{sM[0], sLo[0], sScale[0], a.c};
+    const QuantScalars s = sQ[0];
+    const bool wide = sWide[0] != 0;            // uniform over the workgroup
     const uint64_t q0 = (a.j0 + g.base) >> 3;   // tiles start on multiples of 64 coordinates
-    uint8_t* const pk0 = a.packed + (g.base >> 3) * a.b;
+    uint8_t* const pk0 = packed + (g.base >> 3) * a.b;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const uint32_t o = g.off(idx[h]);
       const uint64_t q = q0 + (o >> 3);
-      const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, a.worker, a.k0, a.k1);
+      const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, stream, a.k0, a.k1);
       uint32_t z[8];
-      quantize8<CFOLD>(v[h], rnd, s, lut, z);
+      if (!wide) quantize8<CFOLD>(v[h], rnd, s, lut, z);
+      else quantize8<CFOLD, true>(v[h], rnd, s, lut, z);
       store_packed8(pk0, o, a.b, z);
     }
   } else {
@@ -505,11 +532,11 @@ __global__ __launch_bounds__(NT, 8) void k_fwd_hi_quant(const QuantArgs a) {
       const uint64_t blk = (g.base >> a.L) + t;
       float M = 0.f, m = 0.f;
       if (blk < (a.d >> a.L)) { M = a.range_M[blk]; m = lower_of(a.range_m, blk, M); }
-      sM[t] = M;
-      sLo[t] = m;
-      sScale[t] = scale16_of(M, m, a.g);
+      bool wide;
+      sQ[t] = quant_scalars(M, m, a.g, a.c, false, wide);
+      sWide[t] = wide;
     }
-    hi_load_to_lds<R>(a.x, g, a.d, lds, t);
+    hi_load_to_lds<R>(xw, g, a.d, lds, t);
     lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, int, float) {});
     __syncthreads();
 #pragma unroll
@@ -518,15 +545,16 @@ __global__ __launch_bounds__(NT, 8) void k_fwd_hi_quant(const QuantArgs a) {
       const uint64_t j = g.coord(idx);
       if (j >= a.d) continue;
       const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
-      const QuantScalars s{sM[bt], sLo[bt], sScale[bt], a.c};
+      const QuantScalars s = sQ[bt];
       const float4 p0 = *reinterpret_cast<const float4*>(&lds[idx]);
       const float4 p1 = *reinterpret_cast<const float4*>(&lds[idx + 4]);
       const float hv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
       const uint64_t q = (a.j0 + j) >> 3;
-      const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, a.worker, a.k0, a.k1);
+      const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, stream, a.k0, a.k1);
       uint32_t z[8];
-      quantize8<false>(hv, rnd, s, lut, z);
-      store_packed8(a.packed, j, a.b, z);
+      if (!sWide[bt]) quantize8<false>(hv, rnd, s, lut, z);
+      else quantize8<false, true>(hv, rnd, s, lut, z);
+      store_packed8(packed, j, a.b, z);
     }
   }
 }

@@ -90,10 +90,10 @@ __device__ __forceinline__ void codes_decode(uint32_t bits, bool ok, const uint3
 // X_i = m + T[z](M-m)/g = T[z] * step_g - M).  One thread loads 16 consecutive coordinates.
 // ---------------------------------------------------------------------------------------------
 struct InvLoArgs {
-  const void* src;         // aggregated stream or packed indices
+  PtrArr src;              // per vector of the launch (grid.y): aggregated stream or packed indices
   const float* range_M;
   const float* range_m;    // or null: m = -M
-  float* ws_x;             // d floats, written
+  float* ws_x;             // d floats per vector of the launch, written
   uint64_t d;
   uint32_t L;
   uint32_t src_bits;       // bits per coordinate in src
@@ -116,13 +116,14 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
   const int idx = 16 * t;
   const uint64_t j = off + lo_map<XO>(idx);
   const bool ok = !GUARD || j < a.d;
+  const uint8_t* const src = static_cast<const uint8_t*>(a.src.p[blockIdx.y]);
 
   // raw bits first, so the load is in flight while the block constants are prepared
   uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   uint32_t y[16];
   const bool staged = !codes_fast_width(a.src_bits);
   if (!staged) {
-    if (ok) codes_load(static_cast<const uint8_t*>(a.src), a.src_bits, j, w, y);
+    if (ok) codes_load(src, a.src_bits, j, w, y);
   } else {
     // Any other width: the tile's eight runs of 1024 codes (128 * bits bytes each, dword aligned) are copied
     // into the still unused tile buffer with coalesced loads; every thread then cuts its sixteen fields out.
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
         const uint64_t jr = off + lo_map<XO>(1024u * r);             // first coordinate of the run
         val[r] = 0;
         if (!GUARD || jr < a.d)                                      // runs exist whole or not at all: 1024 divides d
-          val[r] = reinterpret_cast<const uint32_t*>(static_cast<const uint8_t*>(a.src) + (jr >> 3) * a.src_bits)[t];
+          val[r] = reinterpret_cast<const uint32_t*>(src + (jr >> 3) * a.src_bits)[t];
       }
 #pragma unroll
       for (uint32_t r = 0; r < 8; ++r) stage[r * per_row + t] = val[r];
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
   for (int e = 0; e < 16; e += 4)
     *reinterpret_cast<float4*>(&lds[swz(idx + e)]) = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
 
-  float* dst = a.ws_x + off;
+  float* dst = a.ws_x + (uint64_t)blockIdx.y * a.d + off;
   const uint64_t left = a.d - off;
   lds_stages<4, L1, true, SWZ>(lds, t, [&](int base, int eoff, float val) {
     if (!GUARD || (uint64_t)(base + eoff) < left) dst[lo_map<XO>(base) + lo_map<XO>(eoff)] = val;
@@ -199,9 +200,9 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
 // mode 1: e <- (grad + e) - result (Alg. 3, error-feedback update), out = ef buffer, read and written.
 // ---------------------------------------------------------------------------------------------
 struct InvHiArgs {
-  const float* x;      // half-rotated vector, d floats
-  float* out;          // d floats
-  const void* grad;    // mode 1 only
+  const float* x;      // half-rotated vectors, d floats per vector of the launch (grid.y)
+  PtrArr out;          // per vector: d floats
+  PtrArr grad;         // per vector, mode 1 only
   uint64_t d;
   uint64_t j0;         // global coordinate of x[0] (a multiple of B), for the diagonal's random stream
   TileMap tm;
@@ -210,14 +211,15 @@ struct InvHiArgs {
   float c;
 };
 
-__device__ __forceinline__ float4 inv_finish4(float4 v, uint32_t bits, const InvHiArgs& a, uint64_t j) {
+__device__ __forceinline__ float4 inv_finish4(float4 v, uint32_t bits, const InvHiArgs& a, const float* out,
+                                              const void* grad, uint64_t j) {
   v.x = flip(v.x * a.c, bits & 1u);
   v.y = flip(v.y * a.c, (bits >> 1) & 1u);
   v.z = flip(v.z * a.c, (bits >> 2) & 1u);
   v.w = flip(v.w * a.c, (bits >> 3) & 1u);
   if (a.mode == 1) {
-    float4 x = a.bf16 ? load_grad4<true>(a.grad, j) : load_grad4<false>(a.grad, j);
-    const float4 e = *reinterpret_cast<const float4*>(a.out + j);
+    float4 x = a.bf16 ? load_grad4<true>(grad, j) : load_grad4<false>(grad, j);
+    const float4 e = *reinterpret_cast<const float4*>(out + j);
     x.x += e.x; x.y += e.y; x.z += e.z; x.w += e.w;
     v = make_float4(x.x - v.x, x.y - v.y, x.z - v.z, x.w - v.w);
   }
@@ -231,9 +233,12 @@ __global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
 
   const int t = threadIdx.x;
   const HiGeom<R> g(blockIdx.x, a.tm);
+  const float* const xv = a.x + (uint64_t)blockIdx.y * a.d;
+  float* const out = static_cast<float*>(const_cast<void*>(a.out.p[blockIdx.y]));
+  const void* const grad = a.grad.p[blockIdx.y];
 
   if constexpr (R >= 2) {
-    hi_front<R>(a.x, g, lds, t);
+    hi_front<R>(xv, g, lds, t);
     // 32 consecutive tile indices are 32 consecutive coordinates, or, with 16-wide rows, two aligned halves
     if (t < TILE / 32) {
       if constexpr (HiGeom<R>::W >= 32) {
@@ -253,14 +258,14 @@ __global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
     for (int h = 0; h < 2; ++h) {
       const uint64_t j = g.coord(idx[h]);
       const uint32_t bits = sgn[idx[h] >> 5] >> (idx[h] & 31);
-      const float4 o0 = inv_finish4(make_float4(v[h][0], v[h][1], v[h][2], v[h][3]), bits, a, j);
-      const float4 o1 = inv_finish4(make_float4(v[h][4], v[h][5], v[h][6], v[h][7]), bits >> 4, a, j + 4);
-      *reinterpret_cast<float4*>(a.out + j) = o0;
-      *reinterpret_cast<float4*>(a.out + j + 4) = o1;
+      const float4 o0 = inv_finish4(make_float4(v[h][0], v[h][1], v[h][2], v[h][3]), bits, a, out, grad, j);
+      const float4 o1 = inv_finish4(make_float4(v[h][4], v[h][5], v[h][6], v[h][7]), bits >> 4, a, out, grad, j + 4);
+      *reinterpret_cast<float4*>(out + j) = o0;
+      *reinterpret_cast<float4*>(out + j + 4) = o1;
     }
   } else {
     if (t < TILE / 32) sgn[t] = sign_word(a.j0 + g.coord(32 * t), a.round, a.k0, a.k1);
-    hi_load_to_lds<R>(a.x, g, a.d, lds, t);
+    hi_load_to_lds<R>(xv, g, a.d, lds, t);
     lds_stages<LOG_TILE - R, LOG_TILE, false, PLAIN>(lds, t, [](int, int, float) {});
     __syncthreads();
 #pragma unroll
@@ -270,7 +275,7 @@ __global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
       if (j >= a.d) continue;
       const float4 v = *reinterpret_cast<const float4*>(&lds[idx]);
       const uint32_t bits = sgn[idx >> 5] >> (idx & 31);
-      *reinterpret_cast<float4*>(a.out + j) = inv_finish4(v, bits, a, j);
+      *reinterpret_cast<float4*>(out + j) = inv_finish4(v, bits, a, out, grad, j);
     }
   }
 }

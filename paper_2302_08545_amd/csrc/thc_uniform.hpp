@@ -206,7 +206,9 @@ struct UQuantArgs {
 template <bool BF16>
 __global__ __launch_bounds__(NT) void k_uniform_quant(const UQuantArgs a) {
   __shared__ uint4 lut[256];
-  __shared__ float sM[8], sLo[8], sScale[8], sStep[8];
+  __shared__ QuantScalars sQ[8];
+  __shared__ int sWide[8];
+  __shared__ float sStep[8];
   const int t = threadIdx.x;
   const uint64_t off = (uint64_t)xcd_tile(blockIdx.x, gridDim.x) << LOG_TILE;
   if (t < 256) {
@@ -217,9 +219,9 @@ __global__ __launch_bounds__(NT) void k_uniform_quant(const UQuantArgs a) {
     const uint64_t blk = (off >> a.L) + t;
     float M = 0.f, m = 0.f;
     if (blk < (a.d >> a.L)) { M = a.range_M[blk]; m = lower_of(a.range_m, blk, M); }
-    sM[t] = M;
-    sLo[t] = m;
-    sScale[t] = scale16_of(M, m, a.g);
+    bool wide;
+    sQ[t] = quant_scalars(M, m, a.g, 1.0f, false, wide);
+    sWide[t] = wide;
     sStep[t] = (float)(((double)M - (double)m) / (double)a.g);
   }
   __syncthreads();
@@ -244,14 +246,15 @@ __global__ __launch_bounds__(NT) void k_uniform_quant(const UQuantArgs a) {
     }
     const float hv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
     const int bt = a.L < LOG_TILE ? (idx >> a.L) : 0;
-    const QuantScalars s{sM[bt], sLo[bt], sScale[bt], 1.0f};
+    const QuantScalars s = sQ[bt];
     const uint64_t q = (a.j0 + j) >> 3;
     const uint4 rnd = philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), a.round, a.worker, a.k0, a.k1);
     uint32_t z[8];
-    quantize8<true>(hv, rnd, s, lut, z);          // no scaling: the values are final
+    if (!sWide[bt]) quantize8<true>(hv, rnd, s, lut, z);   // no scaling: the values are final (c = 1)
+    else quantize8<true, true>(hv, rnd, s, lut, z);
     store_packed8(a.packed, j, a.b, z);
     if (a.ef_update) {
-      const float step = sStep[bt], lo = sLo[bt];
+      const float step = sStep[bt], lo = s.lo;
       float e[8];
 #pragma unroll
       for (int k = 0; k < 8; ++k) e[k] = hv[k] - ((float)z[k] * step + lo);   // identity table: T[z] = z

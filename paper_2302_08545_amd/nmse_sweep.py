@@ -49,9 +49,7 @@ def sweep(bs=(2, 3, 4), g_max=51, n=10, p=1.0 / 1024, log2d=20, repeats=100, dev
             for r in range(repeats):
                 x = torch.randn(d, generator=gen, device=device, dtype=torch.float32).exp_()   # LogNormal(0, 1)
                 grads = [x] * n                                   # the same gradient on every worker
-                api.thc_prepare_range(P, r, grads, None, range_M, ws)
-                for i in range(n):
-                    api.thc_compress(P, i, r, x, None, range_M, packed[i], ws)
+                api.thc_compress_all(P, r, grads, None, range_M, packed, ws)
                 api.thc_aggregate(P, packed, agg)
                 api.thc_decompress(P, r, agg, range_M, out, ws)
                 xd = x.double()

@@ -61,8 +61,7 @@ def test_b3_error_feedback_round():
     gn = [to_np32(x) for x in grads]
     efs0 = [np.zeros(d, dtype=np.float32) for _ in range(n)]
     M_ref = o.prepare_range(P, gn, efs0)
-    R.prepare(0, dg)
-    R.compress_all(0, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+    R.compress_each(0, dg, range_M=torch.from_numpy(M_ref).to(DEV))
     for i in range(n):
         pk, ne = o.compress(P, i, 0, gn[i], efs0[i], M_ref)
         assert_indices_match(R.packed[i].cpu().numpy(), pk, 3)

@@ -34,12 +34,12 @@ def table_for(b, g, p=1 / 32):
 
 
 def both_params(d, block, n, b=4, g=30, agg_bits=8, p=1 / 32, bf16=False, seed=SEED, table=None, order=0,
-                first_block=0):
+                first_block=0, group_log2=0):
     T = table if table is not None else table_for(b, g, p)
     tp = o.t_p_of(p)
     P = o.Params(d=d, block=block, n=n, b=b, g=g, t_p=tp, seed=seed, table=T, agg_bits=agg_bits, order=order)
     L = api.make_params(d, block, n, b, g, tp, seed, T, agg_bits, api.THC_DTYPE_BF16 if bf16 else api.THC_DTYPE_F32,
-                        order, first_block)
+                        order, first_block, group_log2)
     return P, L
 
 
@@ -61,27 +61,33 @@ def assert_indices_match(gpu_packed, ref_packed, b, label=""):
 
 
 class GpuRound:
-    """Device buffers for one configuration and the four calls on them."""
+    """Device buffers for one configuration and the calls on them."""
 
     def __init__(self, L, ef=False):
         self.L = L
         d, n = L.d, L.n
         self.K = d // L.block
-        self.ws = torch.empty(api.thc_workspace_bytes(L), dtype=torch.uint8, device=DEV)
+        self.ws = torch.empty(api.thc_workspace_bytes(L, ef), dtype=torch.uint8, device=DEV)
         self.range_M = torch.zeros(self.K, dtype=torch.float32, device=DEV)
         self.packed = [torch.zeros(d * L.b // 8, dtype=torch.uint8, device=DEV) for _ in range(n)]
         self.agg = torch.zeros(d * L.agg_bits // 8, dtype=torch.uint8, device=DEV)
         self.out = torch.zeros(d, dtype=torch.float32, device=DEV)
         self.efs = [torch.zeros(d, dtype=torch.float32, device=DEV) for _ in range(n)] if ef else None
 
-    def prepare(self, rnd, grads, with_range=True):
-        api.thc_prepare_range(self.L, rnd, grads, self.efs, self.range_M if with_range else None, self.ws)
+    def prepare(self, grads):
+        """thc_prepare_range: the norms and the range, nothing else."""
+        api.thc_prepare_range(self.L, grads, self.efs, self.range_M, self.ws)
 
-    def compress_all(self, rnd, grads, range_M=None):
+    def compress_each(self, rnd, grads, range_M=None):
+        """n calls of thc_compress (one worker each), with this object's range or the caller's."""
         rm = self.range_M if range_M is None else range_M
         for i in range(self.L.n):
             api.thc_compress(self.L, i, rnd, grads[i], None if self.efs is None else self.efs[i], rm,
                              self.packed[i], self.ws)
+
+    def compress_all(self, rnd, grads):
+        """thc_compress_all: range and all n workers' streams in one sweep."""
+        api.thc_compress_all(self.L, rnd, grads, self.efs, self.range_M, self.packed, self.ws)
 
     def aggregate(self):
         api.thc_aggregate(self.L, self.packed, self.agg)
@@ -126,12 +132,12 @@ def test_prepare_range_and_compress(block, K, n):
     grads[0][:block] *= 30.0                     # a block where one worker dominates the norm
     R = GpuRound(L)
     dg = [g.to(DEV) for g in grads]
-    R.prepare(4, dg)
+    R.prepare(dg)
     M_ref = o.prepare_range(P, [to_np32(g) for g in grads])
     M_gpu = R.range_M.cpu().numpy()
     assert np.all(np.abs(M_gpu - M_ref) <= np.abs(M_ref) * 2.0 ** -23), (M_gpu, M_ref)
     # the oracle's range goes into the GPU's compress, so a last-bit difference in M cannot hide anything
-    R.compress_all(4, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+    R.compress_each(4, dg, range_M=torch.from_numpy(M_ref).to(DEV))
     for i in range(n):
         ref, _ = o.compress(P, i, 4, to_np32(grads[i]), None, M_ref)
         assert_indices_match(R.packed[i].cpu().numpy(), ref, L.b, f"worker {i}")
@@ -201,7 +207,7 @@ def test_full_round_on_gpu_ranges(block, K, n, b, g, agg_bits):
     grads = make_grads(d, n, seed=7 * n + b)
     R = GpuRound(L)
     dg = [x.to(DEV) for x in grads]
-    R.prepare(2, dg)
+    R.prepare(dg)
     R.compress_all(2, dg)
     R.aggregate()
     R.decompress(2)
@@ -231,10 +237,10 @@ def test_error_feedback_rounds():
         dg = [x.to(DEV) for x in grads]
         gn = [to_np32(x) for x in grads]
         M_ref = o.prepare_range(P, gn, efs_ref)
-        R.prepare(rnd, dg)
+        R.prepare(dg)
         M_gpu = R.range_M.cpu().numpy()
         assert np.all(np.abs(M_gpu - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
-        R.compress_all(rnd, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+        R.compress_each(rnd, dg, range_M=torch.from_numpy(M_ref).to(DEV))
         new_ref = []
         for i in range(n):
             pk, ne = o.compress(P, i, rnd, gn[i], efs_ref[i], M_ref)
@@ -249,14 +255,13 @@ def test_error_feedback_rounds():
 
 @pytest.mark.parametrize("L,K,n,bf16,order", [(12, 11, 2, False, 0), (16, 5, 2, True, 1), (18, 3, 1, False, 1),
                                                  (21, 2, 1, False, 1)])
-def test_piecewise_processing_matches_the_oracle(L, K, n, bf16, order, monkeypatch):
-    """thc_compress (error-feedback chain) and thc_decompress cut long vectors into pieces that share one part of
-    the workspace.  With the piece forced down to 2^14 coordinates (or one block, if larger) these vectors take
-    several pieces, the last one shorter; packed bytes, error feedback and the output must not change."""
-    monkeypatch.setenv("THC_PIECE_LOG2", "14")
+def test_piecewise_processing_matches_the_oracle(L, K, n, bf16, order):
+    """Every call walks long vectors in groups of whole blocks that share the workspace's slot.  With the group forced
+    down to 2^14 coordinates (or one block, if larger) these vectors take several groups, the last one shorter; packed
+    bytes, error feedback and the output must not change."""
     block = 1 << L
     d = block * K
-    P, Lp = both_params(d, block, n, bf16=bf16, order=order)
+    P, Lp = both_params(d, block, n, bf16=bf16, order=order, group_log2=14)
     R = GpuRound(Lp, ef=True)
     efs_ref = [np.zeros(d, dtype=F32) for _ in range(n)]
     for rnd in range(2):
@@ -264,8 +269,8 @@ def test_piecewise_processing_matches_the_oracle(L, K, n, bf16, order, monkeypat
         dg = [x.to(DEV) for x in grads]
         gn = [to_np32(x) for x in grads]
         M_ref = o.prepare_range(P, gn, efs_ref)
-        R.prepare(rnd, dg)
-        R.compress_all(rnd, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+        R.prepare(dg)
+        R.compress_each(rnd, dg, range_M=torch.from_numpy(M_ref).to(DEV))
         pks = []
         for i in range(n):
             pk, ne = o.compress(P, i, rnd, gn[i], efs_ref[i], M_ref)
@@ -293,9 +298,9 @@ def test_bf16_gradients_with_error_feedback():
     dg = [x.to(DEV) for x in grads]
     gn = [to_np32(x) for x in grads]
     M_ref = o.prepare_range(P, gn, efs0)
-    R.prepare(1, dg)
+    R.prepare(dg)
     assert np.all(np.abs(R.range_M.cpu().numpy() - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
-    R.compress_all(1, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+    R.compress_each(1, dg, range_M=torch.from_numpy(M_ref).to(DEV))
     for i in range(n):
         pk, ne = o.compress(P, i, 1, gn[i], efs0[i], M_ref)
         assert_indices_match(R.packed[i].cpu().numpy(), pk, 4)
@@ -310,10 +315,10 @@ def test_blocks_that_need_a_middle_pass(L):
     grads = make_grads(block, n, seed=L)
     R = GpuRound(Lp, ef=True)
     dg = [x.to(DEV) for x in grads]
-    R.prepare(0, dg)
+    R.prepare(dg)
     gn = [to_np32(x) for x in grads]
     M_ref = o.prepare_range(P, gn, [np.zeros(block, dtype=F32)])
-    R.compress_all(0, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+    R.compress_each(0, dg, range_M=torch.from_numpy(M_ref).to(DEV))
     pk, ne = o.compress(P, 0, 0, gn[0], np.zeros(block, dtype=F32), M_ref)
     assert_indices_match(R.packed[0].cpu().numpy(), pk, 4)
     assert rel_l2(R.efs[0].cpu().numpy(), ne) <= 1e-5
@@ -337,12 +342,12 @@ def test_largest_block_against_closed_forms(order):
     R = GpuRound(Lp)
     x = torch.zeros(B, dtype=torch.float32, device=DEV)
     x[k1], x[k2] = 1.0, 2.0
-    R.prepare(3, [x])
+    R.prepare([x])
     xn = np.zeros(B, dtype=F32)
     xn[k1], xn[k2] = 1.0, 2.0
     M_ref = o.prepare_range(P, [xn])
     assert abs(float(R.range_M.cpu()[0]) - float(M_ref[0])) <= 2.0 ** -23 * float(M_ref[0])
-    R.compress_all(3, [x], range_M=torch.from_numpy(M_ref).to(DEV))
+    R.compress_each(3, [x], range_M=torch.from_numpy(M_ref).to(DEV))
     packed = R.packed[0].cpu().numpy()
     s1 = float(o.rademacher_signs(P.seed, 3, k1, 1)[0])
     s2 = float(o.rademacher_signs(P.seed, 3, k2, 1)[0])
@@ -390,7 +395,7 @@ def test_a_round_captured_in_a_hip_graph_replays_bit_for_bit():
     _, L = both_params(d, block, n, order=1)
     grads = [x.to(DEV) for x in make_grads(d, n, seed=5)]
     E = GpuRound(L, ef=True)
-    E.prepare(4, grads)
+    E.prepare(grads)
     E.compress_all(4, grads)
     E.aggregate()
     E.decompress(4)
@@ -402,13 +407,13 @@ def test_a_round_captured_in_a_hip_graph_replays_bit_for_bit():
     side.wait_stream(torch.cuda.current_stream())
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
-        G.prepare(4, grads)                       # warm-up on the capture stream
+        G.prepare(grads)                       # warm-up on the capture stream
         torch.cuda.synchronize()
         for e in G.efs:
             e.zero_()
         torch.cuda.synchronize()
         with torch.cuda.graph(graph, stream=side):
-            G.prepare(4, grads)
+            G.prepare(grads)
             G.compress_all(4, grads)
             G.aggregate()
             G.decompress(4)
@@ -436,7 +441,7 @@ def test_homomorphism_on_the_library_itself():
     _, L = both_params(d, block, n, order=1)
     grads = [x.to(DEV) for x in make_grads(d, n, seed=12)]
     R = GpuRound(L)
-    R.prepare(9, grads)
+    R.prepare(grads)
     R.compress_all(9, grads)
     R.aggregate()
     R.decompress(9)
@@ -475,8 +480,8 @@ def test_buffers_that_hold_a_slice_of_a_longer_vector(first_block, block, K, n, 
         for i in range(n):
             R.efs[i].copy_(torch.from_numpy(efs_ref[i]))
     M_ref = o.prepare_range(P, gn, efs_ref)
-    R.prepare(7, dg)
-    R.compress_all(7, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+    R.prepare(dg)
+    R.compress_each(7, dg, range_M=torch.from_numpy(M_ref).to(DEV))
     pks = []
     for i in range(n):
         pk, ne = o.compress(P, i, 7, gn[i], None if efs_ref is None else efs_ref[i], M_ref, j0=j0)
@@ -499,7 +504,7 @@ def test_two_slices_reproduce_the_whole_vector_bit_for_bit():
     W = GpuRound(Lw, ef=True)
     for i in range(n):
         W.efs[i].copy_(ef0[i])
-    W.prepare(2, grads)
+    W.prepare(grads)
     W.compress_all(2, grads)
     W.aggregate()
     W.decompress(2)
@@ -510,7 +515,7 @@ def test_two_slices_reproduce_the_whole_vector_bit_for_bit():
         for i in range(n):
             S.efs[i].copy_(ef0[i][a:b])
         gs = [g[a:b] for g in grads]
-        S.prepare(2, gs)
+        S.prepare(gs)
         S.compress_all(2, gs)
         S.aggregate()
         S.decompress(2)
@@ -555,9 +560,9 @@ def test_seeded_random_configurations(L, K, n, b, g, agg_bits, ef, bf16, order, 
         for i in range(n):
             R.efs[i].copy_(torch.from_numpy(efs_ref[i]))
     M_ref = o.prepare_range(P, gn, efs_ref)
-    R.prepare(5, dg)
+    R.prepare(dg)
     assert np.all(np.abs(R.range_M.cpu().numpy() - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
-    R.compress_all(5, dg, range_M=torch.from_numpy(M_ref).to(DEV))
+    R.compress_each(5, dg, range_M=torch.from_numpy(M_ref).to(DEV))
     pks = []
     for i in range(n):
         pk, ne = o.compress(P, i, 5, gn[i], None if efs_ref is None else efs_ref[i], M_ref, j0=j0)
@@ -584,7 +589,7 @@ def test_all_zero_block_and_zero_padding():
         x[2 * block + 100:] = 0                  # a partly padded block
     R = GpuRound(L)
     dg = [x.to(DEV) for x in grads]
-    R.prepare(0, dg)
+    R.prepare(dg)
     R.compress_all(0, dg)
     R.aggregate()
     R.decompress(0)
@@ -602,12 +607,12 @@ def test_all_zero_block_and_zero_padding():
 
 
 @pytest.mark.parametrize("L,order", [(12, 0), (13, 0), (16, 1), (17, 1)])
-@pytest.mark.parametrize("k", [-80, 40, -92, -93, -120])
+@pytest.mark.parametrize("k", [-80, 40, -100, -110, -115, -116, -120])
 def test_very_small_and_very_large_magnitudes(L, order, k):
-    """Inputs scaled by 2^k: the indices must equal the oracle's at every magnitude (binary32 has the exponent range,
-    and the kernels' 2^16-scaled grid and folded 1/sqrt(B) must not leave it); ranges narrower than 2^-100 count as
-    empty on both sides.  M is about 2.8e-3 * 2^k here, so k = -92 is the last magnitude above the cutoff and
-    k = -93 the first below it."""
+    """Inputs scaled by 2^k: the indices must equal the oracle's at every magnitude binary32 can hold.  M is about
+    2.8e-3 * 2^k here.  Down to k = -115 the scale g / (M - m) is a finite binary32 number (from about k = -97 on the
+    kernels leave their 2^16-scaled fast form for the plain one); at k = -116 it overflows and the block counts as
+    empty on both sides; at k = -120 the inputs themselves are subnormal."""
     block, K, n = 1 << L, 2, 2
     d = block * K
     P, Lp = both_params(d, block, n, order=order)
@@ -615,15 +620,15 @@ def test_very_small_and_very_large_magnitudes(L, order, k):
     dg = [x.to(DEV) for x in grads]
     gn = [to_np32(x) for x in grads]
     R = GpuRound(Lp)
-    R.prepare(1, dg)
+    R.prepare(dg)
     M_ref = o.prepare_range(P, gn)
     assert np.all(np.abs(R.range_M.cpu().numpy() - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
     Md = torch.from_numpy(M_ref).to(DEV)
-    R.compress_all(1, dg, range_M=Md)
+    R.compress_each(1, dg, range_M=Md)
     pks = [o.compress(P, i, 1, gn[i], None, M_ref)[0] for i in range(n)]
     for i in range(n):
         assert np.array_equal(R.packed[i].cpu().numpy(), pks[i]), f"worker {i}"
-    if k <= -93:
+    if k <= -116:
         assert all(not pk.any() for pk in pks)
     else:
         assert all(pk.any() for pk in pks)
@@ -642,8 +647,8 @@ def test_truncation_is_taken_like_the_oracle():
     dg = [x.to(DEV) for x in grads]
     M_ref = o.prepare_range(P, [to_np32(x) for x in grads])
     for M in (M_ref, (M_ref * F32(0.25)).astype(F32)):
-        R.prepare(6, dg)
-        R.compress_all(6, dg, range_M=torch.from_numpy(M).to(DEV))
+        R.prepare(dg)
+        R.compress_each(6, dg, range_M=torch.from_numpy(M).to(DEV))
         for i in range(n):
             ref, _ = o.compress(P, i, 6, to_np32(grads[i]), None, M)
             assert_indices_match(R.packed[i].cpu().numpy(), ref, 4)
@@ -655,15 +660,14 @@ def test_truncation_is_taken_like_the_oracle():
             assert lo_frac > 0.25 and hi_frac > 0.25
 
 
-def test_caller_supplied_range_without_the_range_kernel():
+def test_caller_supplied_range_without_thc_prepare_range():
     block, n = 1 << 13, 2
     P, L = both_params(2 * block, block, n)
     grads = make_grads(2 * block, n, seed=13)
     R = GpuRound(L)
     dg = [x.to(DEV) for x in grads]
-    R.prepare(0, dg, with_range=False)           # only the half-rotated vectors
     M = np.array([3e-3, 5e-3], dtype=F32)
-    R.compress_all(0, dg, range_M=torch.from_numpy(M).to(DEV))
+    R.compress_each(0, dg, range_M=torch.from_numpy(M).to(DEV))
     for i in range(n):
         ref, _ = o.compress(P, i, 0, to_np32(grads[i]), None, M)
         assert_indices_match(R.packed[i].cpu().numpy(), ref, 4)
@@ -676,14 +680,14 @@ def test_rounds_and_workers_use_different_random_streams_and_calls_are_determini
     grads = [g, g.clone()]                       # identical gradients on both workers
     R = GpuRound(L)
     dg = [x.to(DEV) for x in grads]
-    R.prepare(0, dg)
+    R.prepare(dg)
     R.compress_all(0, dg)
     a0, a1 = R.packed[0].cpu().numpy().copy(), R.packed[1].cpu().numpy().copy()
     assert not np.array_equal(a0, a1)            # independent rounding per worker (App. A)
-    R.prepare(0, dg)
+    R.prepare(dg)
     R.compress_all(0, dg)
     assert np.array_equal(R.packed[0].cpu().numpy(), a0)      # same inputs, same bytes
-    R.prepare(1, dg)
+    R.prepare(dg)
     R.compress_all(1, dg)
     assert not np.array_equal(R.packed[0].cpu().numpy(), a0)  # D^r and the draws change with the round
 
@@ -705,7 +709,7 @@ def test_vgg16_shape_full_size_sampled_blocks(order):
     grads = [wl.gradient(w, i, device=DEV) for i in range(w.n)]
     R = GpuRound(L)
     rnd = 5
-    R.prepare(rnd, grads)
+    R.prepare(grads)
     R.compress_all(rnd, grads)
     R.aggregate()
     R.decompress(rnd)
@@ -748,11 +752,11 @@ def _round_vs_oracle(w, rnd=1, rounds=1):
     efs_ref = [np.zeros(w.d, dtype=F32) for _ in range(w.n)] if w.ef else None
     for r in range(rnd, rnd + rounds):
         M_ref = o.prepare_range(P, gn, efs_ref)
-        R.prepare(r, grads)
+        R.prepare(grads)
         M_gpu = R.range_M.cpu().numpy()
         assert np.all(np.abs(M_gpu - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
         dM = torch.from_numpy(M_ref).to(DEV)
-        R.compress_all(r, grads, range_M=dM)
+        R.compress_each(r, grads, range_M=dM)
         packed_ref, new_efs = [], []
         for i in range(w.n):
             pk, ne = o.compress(P, i, r, gn[i], None if efs_ref is None else efs_ref[i], M_ref)
@@ -804,7 +808,7 @@ def test_partial_aggregation_with_exact_width_sums():
     grads = make_grads(d, n, seed=23)
     R = GpuRound(L)
     dg = [x.to(DEV) for x in grads]
-    R.prepare(7, dg)
+    R.prepare(dg)
     R.compress_all(7, dg)
     M = R.range_M.cpu().numpy()
     subset = [0, 2, 3, 5, 6, 7]                                   # two stragglers left out
@@ -847,10 +851,10 @@ def test_split_stage_order(L, K, n, ef):
     gn = [to_np32(x) for x in grads]
     efs0 = [np.zeros(d, dtype=F32) for _ in range(n)] if ef else None
     M_ref = o.prepare_range(P, gn, efs0)
-    R.prepare(2, dg)
+    R.prepare(dg)
     assert np.all(np.abs(R.range_M.cpu().numpy() - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
     dM = torch.from_numpy(M_ref).to(DEV)
-    R.compress_all(2, dg, range_M=dM)
+    R.compress_each(2, dg, range_M=dM)
     packed_ref = []
     for i in range(n):
         pk, ne = o.compress(P, i, 2, gn[i], None if efs0 is None else efs0[i], M_ref)

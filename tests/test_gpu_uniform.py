@@ -37,7 +37,7 @@ def test_uniform_round(block, K, n, b, agg_bits, ef, first_block, rotate):
     gen = torch.Generator().manual_seed(5)
     efs0 = [(torch.randn(d, generator=gen) * 2e-4).numpy() for _ in range(n)] if ef else None
     defs = [torch.from_numpy(e).to(DEV) for e in efs0] if ef else None
-    ws = torch.empty(api.thc_workspace_bytes(L), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(api.thc_uniform_workspace_bytes(L, rotate), dtype=torch.uint8, device=DEV)
     rm = torch.zeros(K, dtype=torch.float32, device=DEV)
     rM = torch.zeros(K, dtype=torch.float32, device=DEV)
     packed = [torch.zeros(d * b // 8, dtype=torch.uint8, device=DEV) for _ in range(n)]
@@ -78,7 +78,7 @@ def test_bf16_uniform_plain():
     grads = make_grads(d, n, seed=4, bf16=True)
     dg = [g.to(DEV) for g in grads]
     gn = [to_np32(g) for g in grads]
-    ws = torch.empty(api.thc_workspace_bytes(L), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(api.thc_uniform_workspace_bytes(L, False), dtype=torch.uint8, device=DEV)
     rm = torch.zeros(2, dtype=torch.float32, device=DEV)
     rM = torch.zeros(2, dtype=torch.float32, device=DEV)
     api.thc_uniform_prepare_range(L, 0, dg, None, False, rm, rM, ws)

@@ -34,11 +34,12 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_params_struct_layout_matches_header(tmp_path):
-    # d, block (8+8) n b g agg_bits in_dtype t_p (6*4) seed (8) table (256) stage_order first_block (2*4) = 312 bytes
+    # d, block (8+8) n b g agg_bits in_dtype t_p (6*4) seed (8) table (256) stage_order first_block group_log2
+    # reserved (4*4) = 320 bytes
     import ctypes
     import shutil
     import subprocess
-    assert ctypes.sizeof(api.thc_params) == 312
+    assert ctypes.sizeof(api.thc_params) == 320
     assert api.thc_params.seed.offset == 40 and api.thc_params.table.offset == 48
     # the header is plain C: compile it with gcc and compare every field's offset with the binding's
     gcc = shutil.which("gcc")
@@ -61,10 +62,21 @@ def test_params_struct_layout_matches_header(tmp_path):
 
 def test_workspace_size():
     p = _p()
-    # n*d floats for the half-rotated vectors + one double per min(B, 8192) coordinates per worker
-    assert api.thc_workspace_bytes(p) >= 4 * (1 << 12) * 4 + 4 * 4 * 8
+    # two slots that hold one group of blocks of all n workers + one double per min(B, 8192) coordinates per worker
+    assert api.thc_workspace_bytes(p) >= 2 * 4 * (1 << 12) * 4 + 4 * 4 * 8
+    assert api.thc_workspace_bytes(p, True) == api.thc_workspace_bytes(p, False)
+    # it does not grow with d: the 2^28 vector of the VGG16-shaped workload needs two slots of 2^25 values, not n * d
     big = _p(d=1 << 28, block=1 << 20, n=8)
-    assert 8 * (1 << 28) * 4 <= api.thc_workspace_bytes(big) < 8 * (1 << 28) * 4 * 1.01
+    assert 2 * (1 << 25) * 4 <= api.thc_workspace_bytes(big) < 2 * (1 << 25) * 4 * 1.02
+    # n * block when one block of every worker is more than a group: 32 workers with 2^22 blocks
+    wide = _p(d=372 << 22, block=1 << 22, n=32, agg_bits=16)
+    assert 2 * 32 * (1 << 22) * 4 <= api.thc_workspace_bytes(wide) < 2 * 32 * (1 << 22) * 4 * 1.1
+    small = _p(d=1 << 28, block=1 << 20, n=8, group_log2=22)
+    assert api.thc_workspace_bytes(small) < api.thc_workspace_bytes(big) / 3
+    # the uniform variant with rotation keeps all n rotated vectors
+    u = api.make_params(1 << 20, 1 << 12, 4, 4, 15, 2.0, 7, list(range(16)), 8)
+    assert api.thc_uniform_workspace_bytes(u, True) >= 4 * (1 << 20) * 4
+    assert api.thc_uniform_workspace_bytes(u, False) < (1 << 20)
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -87,18 +99,21 @@ def test_workspace_size():
     (dict(n=16, agg_bits=8), -3),
     (dict(d=1 << 40, block=1 << 20), -1),      # more tiles than a 32-bit grid index
     (dict(stage_order=2), -1),
+    (dict(group_log2=9), -1),
+    (dict(group_log2=41), -1),
 ])
 def test_validation_codes(kw, code):
     p = _p(**kw)
     L = api.lib()
     import ctypes as C
     out = C.c_size_t(0)
-    assert L.thc_workspace_bytes(C.byref(p), C.byref(out)) == code
+    assert L.thc_workspace_bytes(C.byref(p), 0, C.byref(out)) == code
     # the compute entry points validate first and return the same code without touching the device
     assert L.thc_aggregate(C.byref(p), None, None, None) == code
     assert L.thc_decompress(C.byref(p), 0, None, None, None, None, None) == code
     assert L.thc_compress(C.byref(p), 0, 0, None, None, None, None, None, None) == code
-    assert L.thc_prepare_range(C.byref(p), 0, None, None, None, None, None) == code
+    assert L.thc_prepare_range(C.byref(p), None, None, None, None, None) == code
+    assert L.thc_compress_all(C.byref(p), 0, None, None, None, None, None, None) == code
 
 
 def test_null_and_misaligned_pointers_are_rejected_on_the_host():
@@ -111,8 +126,13 @@ def test_null_and_misaligned_pointers_are_rejected_on_the_host():
     assert L.thc_compress(C.byref(p), 4, 0, None, None, 16, 16, 16, None) == -1  # worker id out of range
     assert L.thc_compress(C.byref(p), 0, 1 << 32, None, None, 16, 16, 16, None) == -1   # round must fit 32 bits
     arr = (C.c_void_p * 4)(16, 16, 16, 8)
-    assert L.thc_prepare_range(C.byref(p), 0, arr, None, 16, 16, None) == -1    # one misaligned gradient
-    assert L.thc_workspace_bytes(None, None) == -1
+    assert L.thc_prepare_range(C.byref(p), arr, None, 16, 16, None) == -1    # one misaligned gradient
+    assert L.thc_prepare_range(C.byref(p), (C.c_void_p * 4)(16, 16, 16, 16), None, None, 16, None) == -1   # no range
+    assert L.thc_compress(C.byref(p), 0, 0, None, None, 16, 16, 16, None) == -1   # no gradient
+    pk = (C.c_void_p * 4)(16, 16, 16, 16)
+    assert L.thc_compress_all(C.byref(p), 0, arr, None, 16, pk, 16, None) == -1   # one misaligned gradient
+    assert L.thc_compress_all(C.byref(p), 0, pk, None, 16, (C.c_void_p * 4)(16, 16, 0, 16), 16, None) == -1
+    assert L.thc_workspace_bytes(None, 0, None) == -1
 
 
 def test_threshold_matches_definition():

@@ -626,22 +626,27 @@ def test_a_slice_with_its_offset_reproduces_the_whole_vector():
     assert not np.array_equal(pk0, pks[0])
 
 
-def test_power_of_two_scaling_leaves_the_indices_alone_down_to_the_narrow_range_cutoff():
+def test_power_of_two_scaling_leaves_the_indices_alone_down_to_where_the_scale_overflows():
     """Every step up to the index is homogeneous of degree one or zero in the input, and scaling by a power of two
-    is exact in binary32: the packed bytes must not change and the estimate must scale exactly, as long as the range
-    stays above the 2^-100 cutoff below which a block counts as empty."""
+    is exact in binary32: the packed bytes must not change and the estimate must scale exactly.  That holds down to
+    the point where g / (M - m) no longer is a finite binary32 number: from there on the block counts as empty."""
     P = _params(d=2048, block=1024, n=2)
     rng = np.random.default_rng(5)
     grads = [rng.standard_normal(P.d).astype(np.float32) * 1e-3 for _ in range(P.n)]
     M, packed, Y, out, _ = o.thc_round(P, 1, grads)
-    for k in (-40, 30, -80):
+    for k in (-40, 30, -80, -100, -110, -115):
         s = np.float32(2.0 ** k)
         Ms, packed_s, Ys, out_s, _ = o.thc_round(P, 1, [g * s for g in grads])
         assert np.array_equal(Ms, M * s)
-        assert all(np.array_equal(a, b) for a, b in zip(packed_s, packed))
-        assert np.array_equal(Ys, Y) and np.array_equal(out_s, out * s)
-    # far below the cutoff: the block is empty, all indices are 0 and it decodes to m = -M in the rotated domain
-    s = np.float32(2.0 ** -110)
+        assert np.all(np.isfinite(np.float64(P.g) / (2.0 * Ms.astype(np.float64))).astype(bool))
+        assert all(np.array_equal(a, b) for a, b in zip(packed_s, packed)), k
+        assert np.array_equal(Ys, Y)
+        if k >= -100:                      # below that the smallest outputs are subnormal and round
+            assert np.array_equal(out_s, out * s)
+    # M = 2.7e-38: g / (2 M) = 5.6e38 is beyond binary32: the block is empty, all indices are 0 and it decodes to
+    # m = -M in the rotated domain
+    s = np.float32(2.0 ** -116)
     Ms, packed_s, Ys, _, _ = o.thc_round(P, 1, [g * s for g in grads])
-    assert np.all(Ms > 0) and np.all(2.0 * Ms.astype(np.float64) < o.MIN_WIDTH)
+    with np.errstate(over="ignore"):
+        assert np.all(Ms > 0) and np.all(np.isinf((np.float64(P.g) / (2.0 * Ms.astype(np.float64))).astype(np.float32)))
     assert all(not pk.any() for pk in packed_s) and not Ys.any()
