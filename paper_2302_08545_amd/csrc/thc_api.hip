@@ -164,16 +164,19 @@ TileMap lo_tilemap(const Plan& pl, uint64_t len) {
 }
 
 // ---- workspace layout --------------------------------------------------------------------------------------
-// [0, 256)        reserved
-// slot 0, slot 1  the half-rotated vectors of one group of blocks: slot_floats(p) binary32 values each
-// partials        n * (d >> min(L, 13)) binary64 partial sums of squares (one per 8192 coordinates, or per block)
+// [0, 256)   status word of the last single-launch sweep (0 = fine), rest reserved
+// ring       the half-rotated vectors in flight: one group of blocks (launch-by-launch path) or a few block-sized
+//            slots per vector (single-launch path); ring_floats(p, ef) binary32 values
+// partials   n * (d >> min(L, 13)) binary64 partial sums of squares (one per 8192 coordinates, or per block)
+// sync       counters of the single-launch path, K * SYNC_PER_UNIT words
+// lut        device copy of the quantizer's grid-cell table, 256 words
 //
-// A group is a run of whole blocks of every vector in the call, sized so that the group's intermediate (all
-// vectors of the call together) is about 2^group_log2 coordinates: its writer and its reader then follow each other
-// closely enough for the intermediate to still sit in the 256 MB memory-side cache, and the workspace does not grow
+// Launch-by-launch path: a group is a run of whole blocks of every vector in the call, sized so that the group's
+// intermediate (all vectors of the call together) is about 2^group_log2 coordinates; the workspace does not grow
 // with d.  Random streams are indexed by global coordinate, so the grouping never changes a result.
 constexpr size_t WS_HEADER = 256;
-constexpr uint32_t DEFAULT_GROUP_LOG2 = 25;
+constexpr uint32_t DEFAULT_GROUP_LOG2 = 27;
+constexpr uint32_t RESIDENT_WORKGROUPS = 1024;   // 256 compute units x 4 workgroups of 512 threads
 
 uint64_t group_coords(const thc_params* p, uint32_t W) {
   const uint64_t target = 1ull << (p->group_log2 ? p->group_log2 : DEFAULT_GROUP_LOG2);
@@ -183,19 +186,70 @@ uint64_t group_coords(const thc_params* p, uint32_t W) {
   return gc;
 }
 
-uint64_t slot_floats(const thc_params* p) {
-  const uint64_t one = group_coords(p, 1), all = (uint64_t)p->n * group_coords(p, p->n);
-  return one > all ? one : all;
+// Shape of the single-launch sweep over W vectors (thc_pipeline.hpp), or ok = false where it does not apply:
+// it takes the split stage order, blocks of 2^17 .. 2^22 coordinates, at least four blocks, and the default grouping.
+struct PipeShape {
+  bool ok;
+  uint32_t nphase, lag, slots;
+};
+
+PipeShape pipe_shape(const thc_params* p, const Plan& pl, uint32_t W, bool ef) {
+  PipeShape sh{};
+  const uint64_t K = p->d / p->block;
+  sh.ok = pl.split && pl.nmid == 0 && pl.L >= 17 && K >= 4 && K <= 65536 && p->group_log2 == 0;
+  sh.nphase = ef ? 4 : 2;
+  // A consumer should find its producers finished: they are `lag` steps ahead, a step being nphase * Tu workgroups,
+  // of which about RESIDENT_WORKGROUPS run at any time.
+  const uint64_t per_step = (uint64_t)sh.nphase * ((uint64_t)W << pl.R);
+  sh.lag = 1 + (uint32_t)((RESIDENT_WORKGROUPS + per_step - 1) / per_step);
+  sh.slots = (sh.nphase - 1) * sh.lag + 2;
+  return sh;
+}
+
+uint64_t ring_floats(const thc_params* p, const Plan& pl, bool ef) {
+  uint64_t need = group_coords(p, 1);
+  const uint64_t all = (uint64_t)p->n * group_coords(p, p->n);
+  if (all > need) need = all;
+  for (uint32_t W : {1u, p->n}) {
+    const PipeShape sh = pipe_shape(p, pl, W, ef);
+    if (sh.ok && (uint64_t)sh.slots * W * p->block > need) need = (uint64_t)sh.slots * W * p->block;
+  }
+  return need;
 }
 
 size_t partial_count(const thc_params* p, const Plan& pl) { return (size_t)p->n * (size_t)(p->d >> pl.L1); }
 
-float* ws_slot(void* ws, const thc_params* p, int which) {
-  return reinterpret_cast<float*>(static_cast<char*>(ws) + WS_HEADER) + (size_t)which * slot_floats(p);
+size_t sync_words(const thc_params* p) {
+  const uint64_t K = p->d / p->block;
+  return K <= 65536 ? (size_t)K * SYNC_PER_UNIT : 0;
 }
 
-double* ws_partials(void* ws, const thc_params* p) {
-  return reinterpret_cast<double*>(static_cast<char*>(ws) + WS_HEADER + 2 * slot_floats(p) * sizeof(float));
+struct WsLayout {
+  uint32_t* status;
+  float* ring;
+  double* partials;
+  uint32_t* sync;
+  uint32_t* lut;
+  size_t bytes;
+};
+
+// The ring is sized for error feedback whenever the caller asked for it in thc_workspace_bytes; the calls take
+// the layout that goes with what they are given (ef or not), which is the same or smaller.
+WsLayout ws_layout(void* ws, const thc_params* p, const Plan& pl, bool ef) {
+  char* base = static_cast<char*>(ws);
+  WsLayout w{};
+  size_t at = WS_HEADER;
+  w.status = reinterpret_cast<uint32_t*>(base);
+  w.ring = reinterpret_cast<float*>(base + at);
+  at += ring_floats(p, pl, ef) * sizeof(float);
+  w.partials = reinterpret_cast<double*>(base + at);
+  at += partial_count(p, pl) * sizeof(double);
+  w.sync = reinterpret_cast<uint32_t*>(base + at);
+  at += sync_words(p) * sizeof(uint32_t);
+  w.lut = reinterpret_cast<uint32_t*>(base + at);
+  at += 256 * sizeof(uint32_t);
+  w.bytes = at + 256;
+  return w;
 }
 
 uint64_t tiles_of(uint64_t d) { return (d + TILE - 1) / TILE; }
@@ -363,14 +417,98 @@ struct Forward {
   hipStream_t s;
 };
 
+template <int R>
+void launch_pipe_forward(const PipeArgs& a, bool bf16, bool ef, unsigned grid, hipStream_t s) {
+  if (bf16) {
+    if (ef) k_pipe_forward<R, true, true><<<dim3(grid), dim3(NT), 0, s>>>(a);
+    else k_pipe_forward<R, true, false><<<dim3(grid), dim3(NT), 0, s>>>(a);
+  } else {
+    if (ef) k_pipe_forward<R, false, true><<<dim3(grid), dim3(NT), 0, s>>>(a);
+    else k_pipe_forward<R, false, false><<<dim3(grid), dim3(NT), 0, s>>>(a);
+  }
+}
+
+// The whole sweep as one launch (plus a small one that clears the counters).
+void run_forward_pipe(const Forward& f, const Plan& pl, const PipeShape& sh) {
+  const thc_params* p = f.p;
+  const bool bf16 = p->in_dtype == THC_DTYPE_BF16, ef = f.efs != nullptr;
+  const WsLayout wl = ws_layout(f.ws, p, pl, ef);
+  const uint32_t K = (uint32_t)(p->d / p->block);
+
+  PipeSetupArgs su{};
+  su.sync = wl.sync;
+  su.nsync = (uint64_t)K * SYNC_PER_UNIT;
+  su.status = wl.status;
+  su.lut_out = wl.lut;
+  fill_lut(p, su.lut);
+  const unsigned setup_grid = (unsigned)((su.nsync + 4095) / 4096);
+  k_pipe_setup<<<dim3(setup_grid ? setup_grid : 1), dim3(256), 0, f.s>>>(su);
+
+  PipeArgs a{};
+  for (uint32_t i = 0; i < f.W; ++i) {
+    a.grads.p[i] = f.grads[i];
+    if (ef) a.efs.p[i] = f.efs[i];
+    a.packed.p[i] = f.packed[i];
+  }
+  a.ring = wl.ring;
+  a.partials = wl.partials;
+  a.pstride = p->d >> pl.L1;
+  a.range_M = f.range_out ? f.range_out : const_cast<float*>(f.range_in);
+  a.lut = wl.lut;
+  a.sync = wl.sync;
+  a.status = wl.status;
+  a.d = p->d;
+  a.j0 = base_coord(p);
+  a.lo_tm = pl.lo;
+  a.hi_tm = pl.hi;
+  a.L = (uint32_t)pl.L;
+  a.W = f.W;
+  a.K = K;
+  a.slots = sh.slots;
+  a.lag = sh.lag;
+  a.nphase = sh.nphase;
+  a.compute_range = f.range_out ? 1u : 0u;
+  a.b = p->b;
+  a.g = p->g;
+  a.round = (uint32_t)f.round;
+  a.worker0 = f.worker0;
+  a.k0 = (uint32_t)p->seed;
+  a.k1 = (uint32_t)(p->seed >> 32);
+  a.bf16 = bf16;
+  a.c = (float)(1.0 / std::sqrt((double)p->block));
+  a.t_p = p->t_p;
+  std::memcpy(a.table, p->table, 256);
+  const uint64_t Tu = (uint64_t)f.W << pl.R;
+  const uint64_t steps = (uint64_t)K + (uint64_t)(sh.nphase - 1) * sh.lag;
+  const uint64_t grid = steps * ((Tu >> 3) * sh.nphase + 1) * 8;
+  switch (pl.R) {
+    case 4: launch_pipe_forward<4>(a, bf16, ef, (unsigned)grid, f.s); break;
+    case 5: launch_pipe_forward<5>(a, bf16, ef, (unsigned)grid, f.s); break;
+    case 6: launch_pipe_forward<6>(a, bf16, ef, (unsigned)grid, f.s); break;
+    case 7: launch_pipe_forward<7>(a, bf16, ef, (unsigned)grid, f.s); break;
+    case 8: launch_pipe_forward<8>(a, bf16, ef, (unsigned)grid, f.s); break;
+    default: launch_pipe_forward<9>(a, bf16, ef, (unsigned)grid, f.s); break;
+  }
+}
+
 void run_forward(const Forward& f) {
   const thc_params* p = f.p;
   const Plan pl = make_plan(p->block, p->stage_order);
+  {
+    const PipeShape sh = pipe_shape(p, pl, f.W, f.efs != nullptr);
+    const uint64_t Tu = (uint64_t)f.W << pl.R;
+    const uint64_t grid = ((uint64_t)(p->d / p->block) + (uint64_t)(sh.nphase - 1) * sh.lag) * ((Tu >> 3) * sh.nphase + 1) * 8;
+    if (sh.ok && grid < (1ull << 31)) {
+      run_forward_pipe(f, pl, sh);
+      return;
+    }
+  }
   const bool bf16 = p->in_dtype == THC_DTYPE_BF16;
   const size_t in_size = bf16 ? 2 : 4;
   const uint64_t gc = group_coords(p, f.W);
-  float* const slot = ws_slot(f.ws, p, 0);
-  double* const partials = ws_partials(f.ws, p);
+  const WsLayout wl = ws_layout(f.ws, p, pl, f.efs != nullptr);
+  float* const slot = wl.ring;
+  double* const partials = wl.partials;
   const float* const range = f.range_out ? f.range_out : f.range_in;
 
   QuantArgs q{};
@@ -458,9 +596,8 @@ int thc_workspace_bytes(const thc_params* p, int ef_enabled, size_t* bytes_out) 
   const int rc = validate(p);
   if (rc) return rc;
   if (!bytes_out) return THC_EINVAL;
-  (void)ef_enabled;   // the error-feedback update reuses the slot its group has just been quantized from
   const Plan pl = make_plan(p->block, p->stage_order);
-  *bytes_out = WS_HEADER + 2 * slot_floats(p) * sizeof(float) + partial_count(p, pl) * sizeof(double) + 256;
+  *bytes_out = ws_layout(nullptr, p, pl, ef_enabled != 0).bytes;
   return THC_OK;
 }
 
@@ -516,7 +653,7 @@ int thc_prepare_range(const thc_params* p, const void* const* grads, const float
   // The same partial sums, in the same order, as the first pass of thc_compress_all takes them group by group: both
   // give the same M bit for bit.
   const bool bf16 = p->in_dtype == THC_DTYPE_BF16;
-  double* const partials = ws_partials(ws, p);
+  double* const partials = ws_layout(ws, p, pl, false).partials;
   FwdLoArgs a{};
   for (uint32_t i = 0; i < p->n; ++i) {
     a.grads.p[i] = grads[i];
@@ -623,7 +760,7 @@ int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const f
   if (!aligned16(agg) || !aligned16(out) || !aligned16(ws)) return THC_EINVAL;
   const Plan pl = make_plan(p->block, p->stage_order);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  float* const slot = ws_slot(ws, p, 0);
+  float* const slot = ws_layout(ws, p, pl, false).ring;
   InvLoArgs lo{};
   lo.L = (uint32_t)pl.L;
   lo.src_bits = p->agg_bits;

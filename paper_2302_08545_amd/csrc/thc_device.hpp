@@ -1,8 +1,8 @@
 // Device-side building blocks shared by the THC kernels (gfx950, wave64).
 //
-// Numeric contract: every butterfly is one binary32 add and one binary32 subtract, stages run in
-// ascending stride order, and nothing is contracted into a fused multiply-add unless written as
-// __builtin_fmaf.  The file must be compiled with -ffp-contract=off.
+// Numeric contract: every butterfly is one binary32 add and one binary32 subtract, stages run in the order
+// thc_params.stage_order fixes (the host hands each pass its bits as a TileMap), and nothing is contracted into a
+// fused multiply-add unless written as __builtin_fmaf.  The file must be compiled with -ffp-contract=off.
 #pragma once
 
 #include <hip/hip_runtime.h>

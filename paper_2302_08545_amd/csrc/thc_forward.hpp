@@ -40,24 +40,29 @@ __device__ __forceinline__ float4 load_grad4(const void* g, uint64_t j) {
   }
 }
 
-// One workgroup per tile (grid = (tiles, n workers)): measured on MI355X this streams faster than a
-// persistent grid with software prefetch, the hardware dispatcher keeps four workgroups per CU in flight.
-// NORM_ONLY: stop after the partial sums of squares (the norm exchange of Alg. 3 on its own): same sums, same order.
-template <int L1, bool BF16, bool EF, bool XO, bool NORM_ONLY = false>
-__global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
+struct alignas(16) SmemLo {
+  float lds[TILE_PAD];
+  uint32_t sgn[TILE / 32];
+  double wsum[4][NT / 64];
+};
+
+// One tile of the pass: tile index `tile` of vector `worker`; `dst` is where coordinate 0 of that vector's
+// half-rotated image lives (the tile's results go to dst[offset in the vector]).
+template <int L1, bool BF16, bool EF, bool XO, bool NORM_ONLY, class A>
+__device__ __forceinline__ void fwd_lo_tile(const A& a, uint32_t tile, uint32_t worker, float* dst_vec,
+                                            SmemLo& sm) {
   static_assert(!XO || L1 == LOG_TILE, "the row-split tile needs blocks of at least 2^16");
   // Vectors are multiples of B, so only blocks shorter than a tile can leave the last tile partial.
   constexpr bool GUARD = L1 < LOG_TILE;
-  __shared__ __align__(16) float lds[TILE_PAD];
-  __shared__ uint32_t sgn[TILE / 32];
-  __shared__ double wsum[4][NT / 64];
+  float* const lds = sm.lds;
+  uint32_t* const sgn = sm.sgn;
+  double (*const wsum)[NT / 64] = sm.wsum;
 
   const int t = threadIdx.x;
-  const uint32_t worker = blockIdx.y;
   const void* grad = a.grads.p[worker];
   const float* ef = EF ? static_cast<const float*>(a.efs.p[worker]) : nullptr;
   const int wave = t >> 6, lane = t & 63;
-  const uint64_t off = tm_base(a.tm, blockIdx.x);   // coordinate of tile index 0
+  const uint64_t off = tm_base(a.tm, tile);   // coordinate of tile index 0
 
   // all loads of the tile are issued before anything waits on them
   float4 x[4], e[4];
@@ -122,7 +127,7 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
     // one partial per tile (all of it in one block) or, for blocks below 8192, per block of the linear tile
     // the row-split tile is not contiguous: its number stands in (the same block either way); a contiguous tile
     // is numbered by where it lies
-    const uint64_t pidx = XO ? (uint64_t)blockIdx.x : (off >> L1) + t;
+    const uint64_t pidx = XO ? (uint64_t)tile : (off >> L1) + t;
     if (a.partials && pidx < (a.d >> L1)) a.partials[(uint64_t)worker * a.pstride + pidx] = s;
   }
   if constexpr (NORM_ONLY) return;
@@ -140,11 +145,20 @@ __global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
     *reinterpret_cast<float4*>(&lds[phys<PAD>(idx)]) = x[i];
   }
 
-  float* dst = a.ws_x + (uint64_t)worker * a.d + off;
+  float* dst = dst_vec + off;
   const uint64_t left = a.d - off;   // coordinates of this tile that exist (tail tile of a short vector)
   lds_stages<2, L1, true, PAD>(lds, t, [&](int base, int eoff, float v) {
     if (!GUARD || (uint64_t)(base + eoff) < left) dst[lo_map<XO>(base) + lo_map<XO>(eoff)] = v;
   });
+}
+
+// One workgroup per tile (grid = (tiles, n workers)): measured on MI355X this streams faster than a
+// persistent grid with software prefetch, the hardware dispatcher keeps four workgroups per CU in flight.
+// NORM_ONLY: stop after the partial sums of squares (the norm exchange of Alg. 3 on its own): same sums, same order.
+template <int L1, bool BF16, bool EF, bool XO, bool NORM_ONLY = false>
+__global__ __launch_bounds__(NT) void k_fwd_lo(const FwdLoArgs a) {
+  __shared__ SmemLo sm;
+  fwd_lo_tile<L1, BF16, EF, XO, NORM_ONLY>(a, blockIdx.x, blockIdx.y, a.ws_x + (uint64_t)blockIdx.y * a.d, sm);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -159,7 +173,7 @@ struct RangeArgs {
   float t_p;
 };
 
-constexpr int RANGE_NT = 1024;
+constexpr int RANGE_NT = NT;
 
 __device__ __forceinline__ float range_from_sum(double smax, float t_p, uint32_t L) {
   return (float)(((double)t_p * __builtin_sqrt(smax)) / __builtin_sqrt((double)(1ull << L)));
@@ -182,32 +196,41 @@ __global__ __launch_bounds__(256) void k_range_small(const RangeArgs a) {
   a.range_M[k] = range_from_sum(smax, a.t_p, a.L);
 }
 
-// Larger blocks: one workgroup per block.  Sigma x^2 of every worker in a fixed summation order
-// (thread-strided partial sums, wave butterflies, then the 16 wave totals in sequence), the maximum over
-// workers, and M.
-__global__ __launch_bounds__(RANGE_NT) void k_range(const RangeArgs a) {
-  __shared__ double wsum[MAXW][RANGE_NT / 64];
-  const uint64_t k = blockIdx.x;
+struct SmemRange {
+  double wsum[MAXW][RANGE_NT / 64];
+};
+
+// Larger blocks: one workgroup of RANGE_NT threads per block k.  Sigma x^2 of every worker in a fixed summation
+// order (thread-strided partial sums, wave butterflies, then the wave totals in sequence), the maximum over workers,
+// and M, returned by thread 0 (other threads return 0).  `partials` points at this call's first partial sum.
+__device__ __forceinline__ float block_range(const double* partials, uint64_t pstride, uint32_t n, uint32_t ppb,
+                                             uint64_t k, float t_p, uint32_t L, SmemRange& sm) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const uint32_t ppb = 1u << (a.L - a.L1);           // partials per block
-  const uint64_t per_worker = a.pstride;
-  for (uint32_t i = 0; i < a.n; ++i) {
-    const double* p = a.partials + (uint64_t)i * per_worker + k * ppb;
+  for (uint32_t i = 0; i < n; ++i) {
+    const double* p = partials + (uint64_t)i * pstride + k * ppb;
     double s = 0.0;
     for (uint32_t j = t; j < ppb; j += RANGE_NT) s += p[j];
     s = wave_sum(s);
-    if (lane == 0) wsum[i][wave] = s;
+    if (lane == 0) sm.wsum[i][wave] = s;
   }
   __syncthreads();
+  float M = 0.f;
   if (t == 0) {
     double smax = 0.0;
-    for (uint32_t i = 0; i < a.n; ++i) {
+    for (uint32_t i = 0; i < n; ++i) {
       double s = 0.0;
-      for (int w = 0; w < RANGE_NT / 64; ++w) s += wsum[i][w];
+      for (int w = 0; w < RANGE_NT / 64; ++w) s += sm.wsum[i][w];
       smax = s > smax ? s : smax;
     }
-    a.range_M[k] = range_from_sum(smax, a.t_p, a.L);
+    M = range_from_sum(smax, t_p, L);
   }
+  return M;
+}
+
+__global__ __launch_bounds__(RANGE_NT) void k_range(const RangeArgs a) {
+  __shared__ SmemRange sm;
+  const float M = block_range(a.partials, a.pstride, a.n, 1u << (a.L - a.L1), blockIdx.x, a.t_p, a.L, sm);
+  if (threadIdx.x == 0) a.range_M[blockIdx.x] = M;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -451,7 +474,8 @@ __device__ __forceinline__ uint4 quant_lut_entry(uint32_t ent) {
                     ent >> 16);
 }
 
-__device__ __forceinline__ void build_quant_lut(const QuantArgs& a, uint4* lut, int t) {
+template <class A>
+__device__ __forceinline__ void build_quant_lut(const A& a, uint4* lut, int t) {
   if (t < 256) lut[t] = quant_lut_entry(a.lut[t]);
 }
 
@@ -479,21 +503,28 @@ __device__ __forceinline__ float lower_of(const float* range_m, uint64_t blk, fl
   return range_m ? range_m[blk] : -M;
 }
 
-template <int R, bool CFOLD>
-__global__ __launch_bounds__(NT, 8) void k_fwd_hi_quant(const QuantArgs a) {
-  __shared__ __align__(16) float lds[TILE];
-  __shared__ uint4 lut[256];
-  __shared__ QuantScalars sQ[8];
-  __shared__ int sWide[8];
+struct alignas(16) SmemQuant {
+  float lds[TILE];
+  uint32_t lut[256][4];   // uint4 entries
+  float sQ[8][4];         // QuantScalars
+  int sWide[8];
+};
+
+// One tile of the pass: tile index `tile` of the launch's vector `wk`, whose half-rotated image starts at xw.
+template <int R, bool CFOLD, class A>
+__device__ __forceinline__ void hi_quant_tile(const A& a, uint32_t tile, uint32_t wk, const float* xw,
+                                              SmemQuant& sm) {
+  float* const lds = sm.lds;
+  uint4* const lut = reinterpret_cast<uint4*>(sm.lut);
+  QuantScalars* const sQ = reinterpret_cast<QuantScalars*>(sm.sQ);
+  int* const sWide = sm.sWide;
 
   const int t = threadIdx.x;
-  const uint32_t wk = blockIdx.y;                         // worker of the launch
-  const float* const xw = a.x + (uint64_t)wk * a.d;
   uint8_t* const packed = static_cast<uint8_t*>(const_cast<void*>(a.packed.p[wk]));
   const uint32_t stream = a.worker + wk;
 
   if constexpr (R >= 2) {
-    const HiGeom<R> g(blockIdx.x, a.tm);
+    const HiGeom<R> g(tile, a.tm);
     float4 x[4];
     hi_issue_loads<R>(xw, g, t, x);             // tile loads first: everything below overlaps their latency
     build_quant_lut(a, lut, t);
@@ -524,7 +555,7 @@ __global__ __launch_bounds__(NT, 8) void k_fwd_hi_quant(const QuantArgs a) {
       store_packed8(pk0, o, a.b, z);
     }
   } else {
-    const HiGeom<R> g(blockIdx.x, a.tm);
+    const HiGeom<R> g(tile, a.tm);
     build_quant_lut(a, lut, t);
     // per-block scalars; a tile spans more than one block only when B < 8192 (then R == 0)
     const int nblk = a.L < LOG_TILE ? (TILE >> a.L) : 1;
@@ -557,6 +588,12 @@ __global__ __launch_bounds__(NT, 8) void k_fwd_hi_quant(const QuantArgs a) {
       store_packed8(packed, j, a.b, z);
     }
   }
+}
+
+template <int R, bool CFOLD>
+__global__ __launch_bounds__(NT, 8) void k_fwd_hi_quant(const QuantArgs a) {
+  __shared__ SmemQuant sm;
+  hi_quant_tile<R, CFOLD>(a, blockIdx.x, blockIdx.y, a.x + (uint64_t)blockIdx.y * a.d, sm);
 }
 
 }  // namespace thc

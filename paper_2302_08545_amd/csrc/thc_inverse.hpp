@@ -103,20 +103,29 @@ struct InvLoArgs {
   uint8_t table[256];
 };
 
-template <int L1, bool XO>
-__global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
+struct alignas(16) SmemInvLo {
+  float lds[TILE];
+  float sM[8], sStep[8];
+  float tabf[256];
+};
+
+// One tile: tile index `tile` of the launch's vector `vec`; the results go to dst_vec[offset in the vector].
+template <int L1, bool XO, class A>
+__device__ __forceinline__ void inv_lo_tile(const A& a, uint32_t tile, uint32_t vec, float* dst_vec,
+                                            SmemInvLo& sm) {
   static_assert(!XO || L1 == LOG_TILE, "the row-split tile needs blocks of at least 2^16");
   constexpr bool GUARD = L1 < LOG_TILE;
-  __shared__ __align__(16) float lds[TILE];
-  __shared__ float sM[8], sStep[8];
-  __shared__ float tabf[256];
+  float* const lds = sm.lds;
+  float* const sM = sm.sM;
+  float* const sStep = sm.sStep;
+  float* const tabf = sm.tabf;
 
   const int t = threadIdx.x;
-  const uint64_t off = tm_base(a.tm, blockIdx.x);
+  const uint64_t off = tm_base(a.tm, tile);
   const int idx = 16 * t;
   const uint64_t j = off + lo_map<XO>(idx);
   const bool ok = !GUARD || j < a.d;
-  const uint8_t* const src = static_cast<const uint8_t*>(a.src.p[blockIdx.y]);
+  const uint8_t* const src = static_cast<const uint8_t*>(a.src.p[vec]);
 
   // raw bits first, so the load is in flight while the block constants are prepared
   uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -187,11 +196,17 @@ __global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
   for (int e = 0; e < 16; e += 4)
     *reinterpret_cast<float4*>(&lds[swz(idx + e)]) = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
 
-  float* dst = a.ws_x + (uint64_t)blockIdx.y * a.d + off;
+  float* dst = dst_vec + off;
   const uint64_t left = a.d - off;
   lds_stages<4, L1, true, SWZ>(lds, t, [&](int base, int eoff, float val) {
     if (!GUARD || (uint64_t)(base + eoff) < left) dst[lo_map<XO>(base) + lo_map<XO>(eoff)] = val;
   });
+}
+
+template <int L1, bool XO>
+__global__ __launch_bounds__(NT) void k_inv_lo(const InvLoArgs a) {
+  __shared__ SmemInvLo sm;
+  inv_lo_tile<L1, XO>(a, blockIdx.x, blockIdx.y, a.ws_x + (uint64_t)blockIdx.y * a.d, sm);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -211,7 +226,8 @@ struct InvHiArgs {
   float c;
 };
 
-__device__ __forceinline__ float4 inv_finish4(float4 v, uint32_t bits, const InvHiArgs& a, const float* out,
+template <class A>
+__device__ __forceinline__ float4 inv_finish4(float4 v, uint32_t bits, const A& a, const float* out,
                                               const void* grad, uint64_t j) {
   v.x = flip(v.x * a.c, bits & 1u);
   v.y = flip(v.y * a.c, (bits >> 1) & 1u);
@@ -226,16 +242,22 @@ __device__ __forceinline__ float4 inv_finish4(float4 v, uint32_t bits, const Inv
   return v;
 }
 
-template <int R>
-__global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
-  __shared__ __align__(16) float lds[TILE];
-  __shared__ uint32_t sgn[TILE / 32];
+struct alignas(16) SmemInvHi {
+  float lds[TILE];
+  uint32_t sgn[TILE / 32];
+};
+
+// One tile: tile index `tile` of the launch's vector `vec`, whose half-rotated image starts at xv.
+template <int R, class A>
+__device__ __forceinline__ void inv_hi_tile(const A& a, uint32_t tile, uint32_t vec, const float* xv,
+                                            SmemInvHi& sm) {
+  float* const lds = sm.lds;
+  uint32_t* const sgn = sm.sgn;
 
   const int t = threadIdx.x;
-  const HiGeom<R> g(blockIdx.x, a.tm);
-  const float* const xv = a.x + (uint64_t)blockIdx.y * a.d;
-  float* const out = static_cast<float*>(const_cast<void*>(a.out.p[blockIdx.y]));
-  const void* const grad = a.grad.p[blockIdx.y];
+  const HiGeom<R> g(tile, a.tm);
+  float* const out = static_cast<float*>(const_cast<void*>(a.out.p[vec]));
+  const void* const grad = a.grad.p[vec];
 
   if constexpr (R >= 2) {
     hi_front<R>(xv, g, lds, t);
@@ -278,6 +300,12 @@ __global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
       *reinterpret_cast<float4*>(out + j) = inv_finish4(v, bits, a, out, grad, j);
     }
   }
+}
+
+template <int R>
+__global__ __launch_bounds__(NT) void k_inv_hi(const InvHiArgs a) {
+  __shared__ SmemInvHi sm;
+  inv_hi_tile<R>(a, blockIdx.x, blockIdx.y, a.x + (uint64_t)blockIdx.y * a.d, sm);
 }
 
 }  // namespace thc

@@ -89,6 +89,11 @@ class GpuRound:
         """thc_compress_all: range and all n workers' streams in one sweep."""
         api.thc_compress_all(self.L, rnd, grads, self.efs, self.range_M, self.packed, self.ws)
 
+    def status(self):
+        """Status word of the last single-launch sweep on this workspace (0 = fine)."""
+        torch.cuda.synchronize()
+        return int(self.ws[:4].view(torch.int32).cpu()[0])
+
     def aggregate(self):
         api.thc_aggregate(self.L, self.packed, self.agg)
 
@@ -460,6 +465,72 @@ def test_homomorphism_on_the_library_itself():
     # 0.02 * n * 3.1^2 / sum_i (1 + 0.3 i)^2 = 0.042
     true = np.mean([g.double().cpu().numpy() for g in grads], axis=0)
     assert 0.005 < o.nmse(true, together) < 0.045
+
+
+# ----------------------------------------------------------------------------- the single-launch sweep
+@pytest.mark.parametrize("L,K,n,ef,bf16,first_block", [(17, 6, 2, False, False, 0), (17, 5, 3, True, False, 0),
+                                                       (18, 4, 1, True, True, 0), (19, 7, 2, False, True, 3),
+                                                       (20, 4, 2, True, False, 1 << 13), (17, 9, 5, False, False, 0)])
+def test_single_launch_sweep_matches_the_oracle(L, K, n, ef, bf16, first_block):
+    """Split stage order, blocks of 2^17 and more, at least four blocks: thc_compress_all and thc_compress run all
+    passes of all blocks in one launch (blocks follow each other through a ring of slots, workgroups wait on
+    counters).  Range, packed bytes and error feedback must equal the oracle's and the launch-by-launch path's,
+    and the status word must stay 0 (no wait timed out, no workgroup ran on an unexpected XCD)."""
+    block = 1 << L
+    d, j0 = block * K, first_block * block
+    P, Lp = both_params(d, block, n, bf16=bf16, order=1, first_block=first_block)
+    R = GpuRound(Lp, ef=ef)
+    grads = make_grads(d, n, seed=L + K, bf16=bf16)
+    for x in grads:
+        x[2 * block:3 * block] = 0                                # an all-zero block on the way
+    dg = [x.to(DEV) for x in grads]
+    gn = [to_np32(x) for x in grads]
+    efs0 = [to_np32(torch.randn(d, generator=torch.Generator().manual_seed(i)) * 2e-4) for i in range(n)] if ef else None
+    for rnd in (3, 4):
+        if ef:
+            for i in range(n):
+                R.efs[i].copy_(torch.from_numpy(efs0[i]))
+        M_ref = o.prepare_range(P, gn, efs0)
+        R.compress_all(rnd, dg)
+        assert R.status() == 0
+        M_gpu = R.range_M.cpu().numpy()
+        assert np.all(np.abs(M_gpu - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
+        assert ef or M_gpu[2] == 0.0
+        new_efs = []
+        for i in range(n):
+            pk, ne = o.compress(P, i, rnd, gn[i], None if efs0 is None else efs0[i], M_gpu, j0=j0)
+            assert_indices_match(R.packed[i].cpu().numpy(), pk, 4, f"round {rnd} worker {i}")
+            if ef:
+                assert rel_l2(R.efs[i].cpu().numpy(), ne) <= 1e-5, f"round {rnd} worker {i}"
+                new_efs.append(ne)
+        all_packed = [t.clone() for t in R.packed]
+        all_efs = [t.clone() for t in R.efs] if ef else None
+        # one worker at a time (thc_compress, the oracle's range): the same bytes as the oracle with that range
+        dM = torch.from_numpy(M_ref).to(DEV)
+        if ef:
+            for i in range(n):
+                R.efs[i].copy_(torch.from_numpy(efs0[i]))
+        R.compress_each(rnd, dg, range_M=dM)
+        assert R.status() == 0
+        for i in range(n):
+            pk, ne = o.compress(P, i, rnd, gn[i], None if efs0 is None else efs0[i], M_ref, j0=j0)
+            assert_indices_match(R.packed[i].cpu().numpy(), pk, 4, f"round {rnd} worker {i} alone")
+            if ef:
+                assert rel_l2(R.efs[i].cpu().numpy(), ne) <= 1e-5
+        # and the launch-by-launch path (an explicit group size switches the single launch off): bit for bit
+        _, Lg = both_params(d, block, n, bf16=bf16, order=1, first_block=first_block, group_log2=L + 1)
+        G = GpuRound(Lg, ef=ef)
+        if ef:
+            for i in range(n):
+                G.efs[i].copy_(torch.from_numpy(efs0[i]))
+        G.compress_all(rnd, dg)
+        assert torch.equal(G.range_M, torch.from_numpy(M_gpu).to(DEV))
+        for i in range(n):
+            assert torch.equal(G.packed[i], all_packed[i])
+            if ef:
+                assert torch.equal(G.efs[i], all_efs[i])
+        if ef:
+            efs0 = new_efs
 
 
 # ----------------------------------------------------------------------------- slices of a longer vector
