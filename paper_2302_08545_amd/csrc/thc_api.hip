@@ -176,7 +176,18 @@ TileMap lo_tilemap(const Plan& pl, uint64_t len) {
 // with d.  Random streams are indexed by global coordinate, so the grouping never changes a result.
 constexpr size_t WS_HEADER = 256;
 constexpr uint32_t DEFAULT_GROUP_LOG2 = 27;
-constexpr uint32_t RESIDENT_WORKGROUPS = 1024;   // 256 compute units x 4 workgroups of 512 threads
+// From a unit's last first-pass workgroup being dispatched to its range being visible, the chip gets through about
+// this many workgroups (measured on the VGG16-shaped workload: trailing by fewer steps leaves consumers waiting,
+// by more pushes the ring out of the memory-side cache).  A unit's next phase trails by at least that.
+constexpr uint32_t LATENCY_WORKGROUPS = 1024;
+
+uint32_t latency_workgroups() {
+  if (const char* e = std::getenv("THC_PIPE_LATENCY_WG")) {   // tuning aid; any value gives the same results
+    const long v = std::strtol(e, nullptr, 10);
+    if (v >= 1 && v <= (1 << 20)) return (uint32_t)v;
+  }
+  return LATENCY_WORKGROUPS;
+}
 
 uint64_t group_coords(const thc_params* p, uint32_t W) {
   const uint64_t target = 1ull << (p->group_log2 ? p->group_log2 : DEFAULT_GROUP_LOG2);
@@ -198,10 +209,10 @@ PipeShape pipe_shape(const thc_params* p, const Plan& pl, uint32_t W, bool ef) {
   const uint64_t K = p->d / p->block;
   sh.ok = pl.split && pl.nmid == 0 && pl.L >= 17 && K >= 4 && K <= 65536 && p->group_log2 == 0;
   sh.nphase = ef ? 4 : 2;
-  // A consumer should find its producers finished: they are `lag` steps ahead, a step being nphase * Tu workgroups,
-  // of which about RESIDENT_WORKGROUPS run at any time.
+  // A consumer should find its producers finished and published: they are `lag` steps ahead, a step being
+  // nphase * Tu workgroups.
   const uint64_t per_step = (uint64_t)sh.nphase * ((uint64_t)W << pl.R);
-  sh.lag = 1 + (uint32_t)((RESIDENT_WORKGROUPS + per_step - 1) / per_step);
+  sh.lag = 1 + (uint32_t)((latency_workgroups() + per_step - 1) / per_step);
   sh.slots = (sh.nphase - 1) * sh.lag + 2;
   return sh;
 }

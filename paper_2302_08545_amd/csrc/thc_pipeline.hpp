@@ -29,12 +29,12 @@
 namespace thc {
 
 constexpr uint32_t NXCD = 8;
-constexpr uint32_t SYNC_STRIDE = 16;                       // counters sit 64 bytes apart
+constexpr uint32_t SYNC_STRIDE = 64;                       // counters sit 256 bytes apart: polls of one never queue behind updates of another
 constexpr uint32_t SYNC_PHASE = NXCD + 1;                  // per phase: eight tallies and the report count
 constexpr uint32_t SYNC_READY = 4 * SYNC_PHASE;            // range of the unit is in place
 constexpr uint32_t SYNC_DONE = SYNC_READY + 1;             // workgroups of the last phase that are through
 constexpr uint32_t SYNC_PER_UNIT = (SYNC_DONE + 1) * SYNC_STRIDE;
-constexpr uint32_t PIPE_WAIT_SPINS = 400000;               // about a second of waiting before a workgroup gives up
+constexpr uint32_t PIPE_WAIT_SPINS = 250000;               // about a second of waiting before a workgroup gives up
 
 enum : uint32_t { PIPE_OK = 0, PIPE_TIMEOUT = 1, PIPE_STRAY = 2 };
 
@@ -100,17 +100,19 @@ __device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
 }
 
 // Thread 0 waits until *c >= target (bounded; a time-out anywhere ends every other wait too), the workgroup
-// learns the outcome through `flag`.  Ends with the caches invalidated for what the counter announces.
+// learns the outcome through `flag`.  ACQUIRE: ends with the caches invalidated for the data the counter announces
+// (not needed where the counter only says that a buffer may be overwritten).
+template <bool ACQUIRE>
 __device__ __forceinline__ bool pipe_wait(const uint32_t* c, uint32_t target, uint32_t* status, int* flag) {
   if (threadIdx.x == 0) {
     int ok = 0;
     for (uint32_t it = 0; it < PIPE_WAIT_SPINS; ++it) {
       if (ld_agent(c) >= target) { ok = 1; break; }
       if (ld_agent(status) & PIPE_TIMEOUT) break;
-      __builtin_amdgcn_s_sleep(32);
+      __builtin_amdgcn_s_sleep(64);
     }
     if (!ok) __hip_atomic_fetch_or(status, PIPE_TIMEOUT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    if (ACQUIRE) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     *flag = ok;
   }
   __syncthreads();
@@ -168,7 +170,7 @@ __global__ __launch_bounds__(NT, 8) void k_pipe_forward(const PipeArgs P) {
     if (x != 0 || step == 0 || step > P.K) return;
     const uint32_t u = step - 1;
     uint32_t* us = P.sync + (uint64_t)u * SYNC_PER_UNIT;
-    if (!pipe_wait(us + NXCD * SYNC_STRIDE, NXCD, P.status, &flag)) return;
+    if (!pipe_wait<true>(us + NXCD * SYNC_STRIDE, NXCD, P.status, &flag)) return;
     if (P.compute_range) {
       const float M = block_range(P.partials, P.pstride, P.W, TB, u, P.t_p, P.L, *reinterpret_cast<SmemRange*>(raw));
       if (threadIdx.x == 0) {
@@ -197,13 +199,13 @@ __global__ __launch_bounds__(NT, 8) void k_pipe_forward(const PipeArgs P) {
   if (phase == 0) {
     if (u >= P.slots) {   // the slot's previous tenant must be through its last phase
       const uint32_t* old = P.sync + (uint64_t)(u - P.slots) * SYNC_PER_UNIT + SYNC_DONE * SYNC_STRIDE;
-      if (!pipe_wait(old, Tu, P.status, &flag)) return;
+      if (!pipe_wait<false>(old, Tu, P.status, &flag)) return;
     }
     const LoView a{P.grads, P.efs, P.partials, P.pstride, P.d, P.j0, P.round, P.k0, P.k1, P.lo_tm};
     fwd_lo_tile<LOG_TILE, BF16, EF, true, false>(a, gt, w, vec, *reinterpret_cast<SmemLo*>(raw));
     pipe_publish(us, 0, Tu >> 3, P.status);
   } else if (phase == 1) {
-    if (!pipe_wait(us + SYNC_READY * SYNC_STRIDE, 1u, P.status, &flag)) return;
+    if (!pipe_wait<true>(us + SYNC_READY * SYNC_STRIDE, 1u, P.status, &flag)) return;
     const QuantView a{P.range_M, nullptr, P.packed, P.d, P.j0, P.hi_tm, P.L, P.b, P.g, P.round, P.worker0, P.k0, P.k1,
                       P.c, P.lut};
     hi_quant_tile<R, CFOLD>(a, gt, w, vec, *reinterpret_cast<SmemQuant*>(raw));
@@ -216,13 +218,13 @@ __global__ __launch_bounds__(NT, 8) void k_pipe_forward(const PipeArgs P) {
   } else if constexpr (EF) {
     if (phase == 2) {
       // X_i from the indices, inverse first pass into the slot the quantizer has finished with
-      if (!pipe_wait(us + (1 * SYNC_PHASE + NXCD) * SYNC_STRIDE, NXCD, P.status, &flag)) return;
+      if (!pipe_wait<true>(us + (1 * SYNC_PHASE + NXCD) * SYNC_STRIDE, NXCD, P.status, &flag)) return;
       const InvLoView a{P.packed, P.range_M, nullptr, P.d, P.L, P.b, 1u, P.g, P.lo_tm, P.table};
       inv_lo_tile<LOG_TILE, true>(a, gt, w, vec, *reinterpret_cast<SmemInvLo*>(raw));
       pipe_publish(us, 2, Tu >> 3, P.status);
     } else {
       // e <- (grad + e) - RHT^-1(X_i)
-      if (!pipe_wait(us + (2 * SYNC_PHASE + NXCD) * SYNC_STRIDE, NXCD, P.status, &flag)) return;
+      if (!pipe_wait<true>(us + (2 * SYNC_PHASE + NXCD) * SYNC_STRIDE, NXCD, P.status, &flag)) return;
       const InvHiView a{P.efs, P.grads, P.d, P.j0, P.hi_tm, P.round, P.k0, P.k1, 1u, P.bf16, P.c};
       inv_hi_tile<R>(a, gt, w, vec, *reinterpret_cast<SmemInvHi*>(raw));
       if (threadIdx.x == 0)

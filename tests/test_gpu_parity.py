@@ -67,7 +67,7 @@ class GpuRound:
         self.L = L
         d, n = L.d, L.n
         self.K = d // L.block
-        self.ws = torch.empty(api.thc_workspace_bytes(L, ef), dtype=torch.uint8, device=DEV)
+        self.ws = torch.zeros(api.thc_workspace_bytes(L, ef), dtype=torch.uint8, device=DEV)
         self.range_M = torch.zeros(self.K, dtype=torch.float32, device=DEV)
         self.packed = [torch.zeros(d * L.b // 8, dtype=torch.uint8, device=DEV) for _ in range(n)]
         self.agg = torch.zeros(d * L.agg_bits // 8, dtype=torch.uint8, device=DEV)
@@ -205,28 +205,33 @@ def test_decompress(block, K, agg_bits, n):
                                                     (1 << 13, 2, 3, 8, 255, 16), (1 << 14, 2, 10, 3, 12, 7), (1 << 10, 5, 16, 4, 30, 9),
                                                     (1 << 15, 1, 5, 6, 100, 10), (1 << 12, 2, 4, 3, 7, 5)])
 def test_full_round_on_gpu_ranges(block, K, n, b, g, agg_bits):
-    """prepare_range -> compress x n -> aggregate -> decompress, the GPU using its own range."""
+    """thc_prepare_range, thc_compress_all, thc_aggregate, thc_decompress with the GPU's own range: the two range
+    calls agree bit for bit, the range is within 2^-23 of the oracle's, and everything after it equals the oracle
+    working from that very range."""
     d = block * K
     T = table_for(b, g) if g > 2 ** b - 1 else list(range(2 ** b))
     P, L = both_params(d, block, n, b=b, g=g, agg_bits=agg_bits, table=T)
     grads = make_grads(d, n, seed=7 * n + b)
     R = GpuRound(L)
     dg = [x.to(DEV) for x in grads]
+    gn = [to_np32(x) for x in grads]
     R.prepare(dg)
+    M_prep = R.range_M.clone()
     R.compress_all(2, dg)
+    assert torch.equal(R.range_M, M_prep)
     R.aggregate()
     R.decompress(2)
-    M, packed, Y, out, _ = o.thc_round(P, 2, [to_np32(x) for x in grads])
+    M_ref = o.prepare_range(P, gn)
     M_gpu = R.range_M.cpu().numpy()
-    assert np.all(np.abs(M_gpu - M) <= np.abs(M) * 2.0 ** -23)
-    if np.array_equal(M_gpu, M):                 # identical ranges (the usual case): everything is comparable bit for bit
-        for i in range(n):
-            assert_indices_match(R.packed[i].cpu().numpy(), packed[i], b, f"worker {i}")
-        ag = R.agg_numpy()
-        assert np.mean(ag != Y) <= 1e-6 * n
-        assert rel_l2(R.out.cpu().numpy(), out) <= 1e-5
-    # in any case the estimate must be as good as the oracle's
-    mean = np.mean([to_np32(x).astype(np.float64) for x in grads], axis=0)
+    assert np.all(np.abs(M_gpu - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
+    packed = [o.compress(P, i, 2, gn[i], None, M_gpu)[0] for i in range(n)]
+    for i in range(n):
+        assert_indices_match(R.packed[i].cpu().numpy(), packed[i], b, f"worker {i}")
+    Y = o.aggregate(P, packed)
+    assert np.mean(R.agg_numpy() != Y) <= 1e-6 * n
+    out = o.decompress(P, 2, Y, M_gpu)
+    assert rel_l2(R.out.cpu().numpy(), out) <= 1e-5
+    mean = np.mean([x.astype(np.float64) for x in gn], axis=0)
     assert o.nmse(mean, R.out.cpu().numpy()) == pytest.approx(o.nmse(mean, out), rel=0.02)
 
 
@@ -660,21 +665,23 @@ def test_all_zero_block_and_zero_padding():
         x[2 * block + 100:] = 0                  # a partly padded block
     R = GpuRound(L)
     dg = [x.to(DEV) for x in grads]
-    R.prepare(dg)
+    gn = [to_np32(x) for x in grads]
     R.compress_all(0, dg)
     R.aggregate()
     R.decompress(0)
-    M, packed, Y, out, _ = o.thc_round(P, 0, [to_np32(x) for x in grads])
-    assert R.range_M.cpu().numpy()[1] == 0.0 and M[1] == 0.0
+    M_ref = o.prepare_range(P, gn)
+    M_gpu = R.range_M.cpu().numpy()
+    assert M_gpu[1] == 0.0 and M_ref[1] == 0.0
+    assert np.all(np.abs(M_gpu - M_ref) <= np.abs(M_ref) * 2.0 ** -23)
     for i in range(n):
         pk = R.packed[i].cpu().numpy()
         assert np.all(pk[block // 2: block] == 0)
     got = R.out.cpu().numpy()
     assert np.all(got[block:2 * block] == 0)
-    if np.array_equal(R.range_M.cpu().numpy(), M):
-        for i in range(n):
-            assert_indices_match(R.packed[i].cpu().numpy(), packed[i], 4)
-        assert rel_l2(got, out) <= 1e-5
+    packed = [o.compress(P, i, 0, gn[i], None, M_gpu)[0] for i in range(n)]
+    for i in range(n):
+        assert_indices_match(R.packed[i].cpu().numpy(), packed[i], 4)
+    assert rel_l2(got, o.decompress(P, 0, o.aggregate(P, packed), M_gpu)) <= 1e-5
 
 
 @pytest.mark.parametrize("L,order", [(12, 0), (13, 0), (16, 1), (17, 1)])
@@ -763,50 +770,126 @@ def test_rounds_and_workers_use_different_random_streams_and_calls_are_determini
     assert not np.array_equal(R.packed[0].cpu().numpy(), a0)  # D^r and the draws change with the round
 
 
-# ----------------------------------------------------------------------------- the bench configuration
+# ----------------------------------------------------------------------------- the bench configurations
+def checksum64(t):
+    """Sum of the buffer's 64-bit words modulo 2^64 (torch tensor or numpy array of bytes)."""
+    if isinstance(t, np.ndarray):
+        return int(np.frombuffer(t.tobytes(), dtype=np.uint64).sum(dtype=np.uint64))
+    return int(t.view(torch.int64).sum().cpu()) & 0xFFFFFFFFFFFFFFFF
+
+
+def _launch_shape_parity(w, blocks, workers=None, rounds=1, order=1, alone=None):
+    """A workload at the size and in the launch configuration bench.py times it in (thc_compress_all, thc_aggregate,
+    thc_decompress on the whole vectors).  The oracle checks the sampled blocks (blocks are independent THC
+    instances) for the sampled workers, working from the very range the GPU used, which itself must be within 2^-23
+    of the oracle's.  Properties cover the rest: sums never exceed g*n, all-zero blocks decode to exact zeros.
+    `alone`: a worker that is also compressed on its own (thc_compress) with the oracle's range for the sampled
+    blocks."""
+    workers = list(range(w.n)) if workers is None else workers
+    T = o.solve_table(w.b, w.g, w.p)
+    tp = o.t_p_of(w.p)
+    B = w.block
+    P_blk = o.Params(d=B, block=B, n=w.n, b=w.b, g=w.g, t_p=tp, seed=SEED, table=T, agg_bits=w.agg_bits, order=order)
+    L = api.make_params(w.d, B, w.n, w.b, w.g, tp, SEED, T, w.agg_bits,
+                        api.THC_DTYPE_BF16 if w.dtype == "bf16" else api.THC_DTYPE_F32, order)
+    grads = [wl.gradient(w, i, device=DEV) for i in range(w.n)]
+    for i in (0, w.n - 1):
+        print(f"{w.name} input {i}: {wl.checksum(grads[i][:1 << 24])}")
+    R = GpuRound(L, ef=w.ef)
+    compared = 0
+    for rnd in range(rounds):
+        ef_before = {(k, i): R.efs[i][k * B:(k + 1) * B].cpu().numpy() for k in blocks for i in range(w.n)} if w.ef else {}
+        R.compress_all(rnd, grads)
+        assert R.status() == 0
+        R.aggregate()
+        R.decompress(rnd)
+        torch.cuda.synchronize()
+        M_gpu = R.range_M.cpu().numpy()
+        assert int(R.agg.view(torch.uint8 if w.agg_bits == 8 else torch.int16).max()) <= w.g * w.n
+        print(f"{w.name} round {rnd}: packed checksums {[hex(checksum64(t)) for t in R.packed]}, sums {hex(checksum64(R.agg))}")
+        for k in blocks:
+            sl = slice(k * B, (k + 1) * B)
+            gn = [to_np32(g[sl]) for g in grads]
+            efs0 = [ef_before[(k, i)] for i in range(w.n)] if w.ef else None
+            M_ref = o.prepare_range(P_blk, gn, efs0)
+            assert abs(M_gpu[k] - M_ref[0]) <= abs(M_ref[0]) * 2.0 ** -23, f"block {k}"
+            Mk = M_gpu[k:k + 1]
+            for i in workers:
+                pk, ne = o.compress(P_blk, i, rnd, gn[i], None if efs0 is None else efs0[i], Mk, j0=k * B)
+                got = R.packed[i][k * B * w.b // 8:(k + 1) * B * w.b // 8].cpu().numpy()
+                assert_indices_match(got, pk, w.b, f"{w.name} round {rnd} block {k} worker {i}")
+                if w.ef:
+                    assert rel_l2(R.efs[i][sl].cpu().numpy(), ne) <= 1e-5, f"block {k} worker {i}"
+            # the sums of ALL workers' streams as the GPU wrote them, then the estimate from those sums
+            Y = o.aggregate(P_blk, [t[k * B * w.b // 8:(k + 1) * B * w.b // 8].cpu().numpy() for t in R.packed])
+            agg_k = R.agg[k * B * w.agg_bits // 8:(k + 1) * B * w.agg_bits // 8].cpu().numpy()
+            assert np.array_equal(agg_k, o.aggregate_stream(P_blk, Y)), f"block {k}"
+            assert checksum64(agg_k) == checksum64(o.aggregate_stream(P_blk, Y))
+            ref = o.decompress(P_blk, rnd, Y, Mk, j0=k * B)
+            assert rel_l2(R.out[sl].cpu().numpy(), ref) <= 1e-5, f"block {k}"
+            compared += 1
+        if alone is not None and not w.ef:
+            # one worker on its own, the oracle's range injected for the sampled blocks
+            rm = R.range_M.clone()
+            refs = {}
+            for k in blocks:
+                gn = [to_np32(g[k * B:(k + 1) * B]) for g in grads]
+                refs[k] = o.prepare_range(P_blk, gn)
+                rm[k] = float(refs[k][0])
+            pk_all = torch.zeros_like(R.packed[alone])
+            api.thc_compress(L, alone, rnd, grads[alone], None, rm, pk_all, R.ws)
+            assert R.status() == 0
+            for k in blocks:
+                pk, _ = o.compress(P_blk, alone, rnd, to_np32(grads[alone][k * B:(k + 1) * B]), None, refs[k], j0=k * B)
+                assert_indices_match(pk_all[k * B * w.b // 8:(k + 1) * B * w.b // 8].cpu().numpy(), pk, w.b, f"alone, block {k}")
+    assert compared == rounds * len(blocks)
+    return R, grads
+
+
+def _need_memory(gib):
+    free, _ = torch.cuda.mem_get_info()
+    if free < gib * (1 << 30):
+        pytest.skip(f"needs about {gib} GiB of device memory")
+
+
+@pytest.mark.timeout(900)
 @pytest.mark.parametrize("order", [1, 0], ids=["split-order", "ascending-order"])
 def test_vgg16_shape_full_size_sampled_blocks(order):
-    """The 138M-coordinate / 2^28-padded, 8-worker, b=4 configuration in the launch shape bench.py times
-    (bench.py runs the split stage order by default).
-    The oracle checks sampled blocks one by one (blocks are independent THC instances); properties cover
-    the rest: zero padding decodes to exactly zero and aggregated sums never exceed g*n."""
+    """The 138M-coordinate / 2^28-padded, 8-worker, b=4 configuration (bench.py's default; it runs the split order)."""
     w = wl.C3
-    free, _ = torch.cuda.mem_get_info()
-    if free < 30 * (1 << 30):
-        pytest.skip("needs ~22 GB of device memory")
-    T = o.solve_table(w.b, w.g, w.p)
-    P_blk = o.Params(d=w.block, block=w.block, n=w.n, b=w.b, g=w.g, t_p=o.t_p_of(w.p), seed=SEED, table=T, order=order)
-    L = api.make_params(w.d, w.block, w.n, w.b, w.g, o.t_p_of(w.p), SEED, T, w.agg_bits, api.THC_DTYPE_F32, order)
-    grads = [wl.gradient(w, i, device=DEV) for i in range(w.n)]
-    R = GpuRound(L)
-    rnd = 5
-    R.prepare(grads)
-    R.compress_all(rnd, grads)
-    R.aggregate()
-    R.decompress(rnd)
-    torch.cuda.synchronize()
-    M_gpu = R.range_M.cpu().numpy()
+    _need_memory(16)
     first_pad = (w.real + w.block - 1) // w.block          # blocks from here on are all zero
+    blocks = (0, 14, 63, 131, first_pad - 1)               # conv part, FC part, the partly padded block
+    R, _ = _launch_shape_parity(w, blocks, order=order, alone=5 if order == 1 else None)
+    M_gpu = R.range_M.cpu().numpy()
     assert np.all(M_gpu[first_pad:] == 0) and np.all(M_gpu[:first_pad] > 0)
-    assert int(R.agg.max()) <= w.g * w.n
     assert float(R.out[first_pad * w.block:].abs().max()) == 0.0
-    B = w.block
-    for k in (0, 14, 63, 131, first_pad - 1):              # conv part, FC part, the partly padded block
-        sl = slice(k * B, (k + 1) * B)
-        gn = [g[sl].cpu().numpy() for g in grads]
-        M_ref = o.prepare_range(P_blk, gn)
-        assert abs(M_gpu[k] - M_ref[0]) <= abs(M_ref[0]) * 2.0 ** -23
-        if M_gpu[k] != M_ref[0]:
-            continue
-        packed_ref = []
-        for i in range(w.n):
-            pk, _ = o.compress(P_blk, i, rnd, gn[i], None, M_ref, j0=k * B)
-            assert_indices_match(R.packed[i][k * B // 2:(k + 1) * B // 2].cpu().numpy(), pk, w.b, f"block {k} worker {i}")
-            packed_ref.append(pk)
-        Y = o.aggregate(P_blk, packed_ref)
-        assert np.mean(R.agg[sl].cpu().numpy() != Y) <= 1e-5
-        ref = o.decompress(P_blk, rnd, Y, M_ref, j0=k * B)
-        assert rel_l2(R.out[sl].cpu().numpy(), ref) <= 1e-5
+    assert all(int(t[first_pad * w.block // 2:].max()) == 0 for t in R.packed)
+
+
+@pytest.mark.timeout(900)
+def test_resnet50_shape_full_size_all_workers_two_rounds():
+    """One 2^25-point transform over the zero-padded vector, 8 workers, error feedback carried into a second round
+    (launch by launch: the block needs a middle pass).  The oracle transforms three of the eight workers."""
+    _need_memory(8)
+    _launch_shape_parity(wl.C2, (0,), workers=[0, 3, 7], rounds=2)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("w", [wl.C4_B4, wl.C4_B2], ids=lambda w: w.name)
+def test_bert_large_shape_full_size_sampled_blocks(w):
+    """321 blocks of 2^20 (not a multiple of the 64-tile spans the first pass permutes over), 16 workers; 16-bit
+    sums at b = 4, 8-bit sums at b = 2."""
+    _need_memory(40)
+    _launch_shape_parity(w, (0, 63, 64, 320))
+
+
+@pytest.mark.timeout(900)
+def test_gpt2_xl_shape_prefix_all_workers():
+    """The first 48 blocks of 2^22 of the GPT-2-XL-shaped workload (what bench.py --workload c5_gpt2_xl --blocks 48
+    runs): 32 workers, bf16 gradients, error feedback, two rounds; the oracle follows three workers."""
+    _need_memory(70)
+    _launch_shape_parity(wl.shrink(wl.C5, 48), (0, 47), workers=[0, 13, 31], rounds=2)
 
 
 # ----------------------------------------------------------------------------- the other workload recipes
