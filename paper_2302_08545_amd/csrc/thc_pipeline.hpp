@@ -17,11 +17,14 @@
 // raising a status word that the caller can read (nothing hangs; the results are then invalid).
 //
 // Visibility.  On this chip every XCD has its own L2, which holds a producer's stores until they are written back,
-// and workgroups are dealt to the XCDs round-robin (workgroup id mod 8; checked against the hardware XCC id at run
-// time).  The producers of a unit count in per XCD once their stores are acknowledged; the one that completes its
-// XCD's count writes that L2 back (a release fence at agent scope) and reports; consumers wait for all eight
-// reports, invalidate (an acquire fence at agent scope) and read.  Eight write-backs per unit instead of one per
-// workgroup: a release fence per workgroup was measured at 4x to 30x the run time of the whole chain.
+// and consecutive workgroups are dealt to the eight XCDs in turn (from a starting XCD that differs from launch to
+// launch, so a workgroup asks the hardware which XCD it is on).  Every group of eight consecutive workgroups belongs
+// to one unit and phase, hence each XCD runs an eighth of a unit's producers.  They count in per XCD once their stores
+// are acknowledged; the one that completes its XCD's count writes that L2 back (a release fence at agent scope) and
+// reports; consumers wait for all eight reports, invalidate (an acquire fence at agent scope) and read.  Eight
+// write-backs per unit instead of one per workgroup: a release fence per workgroup was measured at 4x to 30x the run
+// time of the whole chain.  Were workgroups ever dealt differently, a count would stay short and the waits would
+// time out into the status word: never a silent wrong result.
 #pragma once
 
 #include "thc_inverse.hpp"
@@ -36,7 +39,7 @@ constexpr uint32_t SYNC_DONE = SYNC_READY + 1;             // workgroups of the 
 constexpr uint32_t SYNC_PER_UNIT = (SYNC_DONE + 1) * SYNC_STRIDE;
 constexpr uint32_t PIPE_WAIT_SPINS = 250000;               // about a second of waiting before a workgroup gives up
 
-enum : uint32_t { PIPE_OK = 0, PIPE_TIMEOUT = 1, PIPE_STRAY = 2 };
+enum : uint32_t { PIPE_OK = 0, PIPE_TIMEOUT = 1 };
 
 struct PipeArgs {
   PtrArr grads, efs, packed;   // W vectors: gradients, error-feedback buffers (or unused), packed outputs
@@ -123,16 +126,11 @@ __device__ __forceinline__ bool pipe_wait(const uint32_t* c, uint32_t target, ui
 
 // The workgroup's stores are done: count it in for its XCD; whoever completes the count writes the XCD's L2 back
 // and reports.
-__device__ __forceinline__ void pipe_publish(uint32_t* unit_sync, uint32_t phase, uint32_t per_xcd, uint32_t* status) {
+__device__ __forceinline__ void pipe_publish(uint32_t* unit_sync, uint32_t phase, uint32_t per_xcd) {
   __builtin_amdgcn_s_waitcnt(0);      // vmcnt(0) expcnt(0) lgkmcnt(0): this wave's stores are acknowledged by the L2
   __syncthreads();
   if (threadIdx.x == 0) {
-    const uint32_t x = blockIdx.x & (NXCD - 1);
-    if (xcc_id() != x) {
-      // not where the round-robin rule says: write back the L2 this workgroup really ran on, and say so
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-      __hip_atomic_fetch_or(status, PIPE_STRAY, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+    const uint32_t x = xcc_id() & (NXCD - 1);     // the XCD whose L2 holds this workgroup's stores
     uint32_t* c = unit_sync + (phase * SYNC_PHASE) * SYNC_STRIDE;
     const uint32_t old = __hip_atomic_fetch_add(c + x * SYNC_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old == per_xcd - 1) {
@@ -203,14 +201,14 @@ __global__ __launch_bounds__(NT, 8) void k_pipe_forward(const PipeArgs P) {
     }
     const LoView a{P.grads, P.efs, P.partials, P.pstride, P.d, P.j0, P.round, P.k0, P.k1, P.lo_tm};
     fwd_lo_tile<LOG_TILE, BF16, EF, true, false>(a, gt, w, vec, *reinterpret_cast<SmemLo*>(raw));
-    pipe_publish(us, 0, Tu >> 3, P.status);
+    pipe_publish(us, 0, Tu >> 3);
   } else if (phase == 1) {
     if (!pipe_wait<true>(us + SYNC_READY * SYNC_STRIDE, 1u, P.status, &flag)) return;
     const QuantView a{P.range_M, nullptr, P.packed, P.d, P.j0, P.hi_tm, P.L, P.b, P.g, P.round, P.worker0, P.k0, P.k1,
                       P.c, P.lut};
     hi_quant_tile<R, CFOLD>(a, gt, w, vec, *reinterpret_cast<SmemQuant*>(raw));
     if constexpr (EF) {
-      pipe_publish(us, 1, Tu >> 3, P.status);
+      pipe_publish(us, 1, Tu >> 3);
     } else {
       if (threadIdx.x == 0)   // every wave's loads from the slot came back before the tile's last barrier
         __hip_atomic_fetch_add(us + SYNC_DONE * SYNC_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -221,7 +219,7 @@ __global__ __launch_bounds__(NT, 8) void k_pipe_forward(const PipeArgs P) {
       if (!pipe_wait<true>(us + (1 * SYNC_PHASE + NXCD) * SYNC_STRIDE, NXCD, P.status, &flag)) return;
       const InvLoView a{P.packed, P.range_M, nullptr, P.d, P.L, P.b, 1u, P.g, P.lo_tm, P.table};
       inv_lo_tile<LOG_TILE, true>(a, gt, w, vec, *reinterpret_cast<SmemInvLo*>(raw));
-      pipe_publish(us, 2, Tu >> 3, P.status);
+      pipe_publish(us, 2, Tu >> 3);
     } else {
       // e <- (grad + e) - RHT^-1(X_i)
       if (!pipe_wait<true>(us + (2 * SYNC_PHASE + NXCD) * SYNC_STRIDE, NXCD, P.status, &flag)) return;

@@ -115,7 +115,8 @@ def gradient(w: Workload, worker: int, device="cpu", seed: int = BASE_SEED) -> t
                 break
             sz = min(sz, real - pos)
             u = _rand(sz, gen, dev) - 0.5                  # Laplace(0, s) by inverse CDF
-            out[pos:pos + sz] = -sc * torch.sign(u) * torch.log1p(-2.0 * u.abs())
+            a = torch.clamp(2.0 * u.abs(), max=1.0 - 2.0 ** -24)   # a draw of exactly 0 would give log(0)
+            out[pos:pos + sz] = -sc * torch.sign(u) * torch.log1p(-a)
             pos += sz
     elif w.kind == "bert":
         gs = _gen("cpu", seed ^ (0xBE27 + worker))
