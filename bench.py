@@ -112,6 +112,8 @@ def main():
                          "each: thc_prepare_range, then thc_compress once per worker")
     ap.add_argument("--group-log2", type=int, default=0,
                     help="thc_params.group_log2 (0 = the library's default; a value switches the single-launch sweep off)")
+    ap.add_argument("--single-launch", action="store_true",
+                    help="thc_params.single_launch: all passes of all blocks in one kernel launch, small workspace")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device-to-device copy five times and exit (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -161,7 +163,7 @@ def main():
     seed = wl.RHT_SEED
     order = api.THC_ORDER_SPLIT if args.stage_order == "split" else api.THC_ORDER_ASCENDING
     L = api.make_params(w.d, w.block, w.n, w.b, w.g, t_p, seed, table, w.agg_bits,
-                        api.THC_DTYPE_BF16 if w.dtype == "bf16" else api.THC_DTYPE_F32, order, 0, args.group_log2)
+                        api.THC_DTYPE_BF16 if w.dtype == "bf16" else api.THC_DTYPE_F32, order, 0, args.group_log2, int(args.single_launch))
 
     grads = [wl.gradient(w, i, device=dev) for i in range(w.n)]
     print("bench input checksums:", json.dumps({f"worker{i}": wl.checksum(grads[i][:1 << 24]) for i in (0, w.n - 1)}),
@@ -255,7 +257,8 @@ def main():
     fwd_ms = stage_ms["prepare_range"] + stage_ms["compress"]
     achieved = fwd_alg_bytes / (fwd_ms * 1e-3) / 1e9
     default_config = (args.stage_order == "split" and not args.block_log2 and not args.agg_bits and args.calls == "all"
-                      and not args.group_log2 and not args.blocks and not args.workers and not args.graph)
+                      and not args.group_log2 and not args.blocks and not args.workers and not args.graph
+                      and not args.single_launch)
     result = {
         "metric": "gradient coords/s (compress+aggregate+decompress), coordinates of the zero-padded vector",
         "value": w.d / per_step,
@@ -272,7 +275,8 @@ def main():
         "config": {"workload": w.name, "d_padded": w.d, "d_real": w.real, "rht_block": w.block, "workers": w.n,
                    "b": w.b, "g": w.g, "agg_bits": w.agg_bits, "error_feedback": w.ef, "input": w.dtype,
                    "stage_order": args.stage_order, "variant": args.variant, "hip_graph": args.graph,
-                   "calls": args.calls, "group_log2": args.group_log2, "workspace_bytes": ws_bytes},
+                   "calls": args.calls, "group_log2": args.group_log2, "single_launch": args.single_launch,
+                   "workspace_bytes": ws_bytes},
         "value_real": w.real / per_step,        # the same time over the coordinates that carry data (no padding)
         "worker_coords_per_s": w.n * w.d / per_step,
         "effective_hbm_GBps": bpc * w.d / per_step / 1e9,
@@ -282,8 +286,9 @@ def main():
         "moved_bytes_per_coord": wl.moved_bytes_per_coord(w),
         "moved_GBps": wl.moved_bytes_per_coord(w) * w.d / per_step / 1e9,
         "stage_ms": stage_ms,
-        "roofline": {"bound": "hbm", "kernel": "k_pipe_forward (thc_compress_all)" if args.calls == "all" else
-                     "thc_prepare_range + n x thc_compress", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": ("k_pipe_forward (thc_compress_all, single launch)" if args.single_launch else
+                                "thc_compress_all: k_fwd_lo + k_range + k_fwd_hi_quant per group of blocks")
+                     if args.calls == "all" else "thc_prepare_range + n x thc_compress", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "algorithmic_bytes": fwd_alg_bytes, "launch_ms": fwd_ms,
                      "traffic": measured_traffic(w.name) if default_config else None},

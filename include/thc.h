@@ -89,10 +89,13 @@ typedef struct thc_params {
   uint8_t  table[256]; /* T[0 .. 2^b-1]; see thc_solve_table                                               */
   uint32_t stage_order;/* THC_ORDER_ASCENDING or THC_ORDER_SPLIT                                           */
   uint32_t first_block;/* index, in the whole vector, of the first block these buffers hold (0 for a whole vector) */
-  uint32_t group_log2; /* 0 = default (25).  The transform's passes walk a vector in groups of whole blocks of about
+  uint32_t group_log2; /* 0 = default (29).  The transform's passes walk a vector in groups of whole blocks of about
                           2^group_log2 coordinates (over all vectors of the call), 10..40: it sizes the workspace
-                          and decides how much of the intermediate stays in the memory-side cache; never a result */
-  uint32_t reserved;   /* 0 */
+                          (which therefore does not grow with d); never a result */
+  uint32_t single_launch; /* 0 or 1.  1: thc_compress and thc_compress_all run all passes of all blocks in ONE kernel
+                          launch where they can (split stage order, blocks of 2^17 .. 2^22, at least four blocks,
+                          group_log2 = 0), blocks following each other through a ring of a few block-sized slots: an
+                          eighth of the workspace at about the same speed.  Never a result.  See thc_sweep_status */
 } thc_params;
 
 /* Library version (major*10000 + minor*100 + patch). */
@@ -102,10 +105,10 @@ int thc_version(void);
 const char* thc_strerror(int status);
 
 /* Bytes of device workspace the calls below need for these parameters (host call, no GPU work).  The workspace
- * holds the half-transformed vectors of one group of blocks (two slots of max(2^group_log2, n * block) binary32
- * values) and one binary64 partial sum of squares per 8192 coordinates per worker; it does not grow with d beyond
- * that.  `ef_enabled` says whether error feedback will be used (the update reuses the group's slot, so the size is
- * the same today; callers should still say). */
+ * holds the half-transformed vectors of one group of blocks (max(2^group_log2, n * block) binary32 values, or the
+ * ring of the single-launch sweep), one binary64 partial sum of squares per 8192 coordinates per worker and the
+ * sweep's counters; it does not grow with d beyond those.  `ef_enabled` says whether error feedback will be used
+ * (the single-launch sweep then needs a longer ring); a workspace sized with ef_enabled = 1 serves both. */
 int thc_workspace_bytes(const thc_params* p, int ef_enabled, size_t* bytes_out /* host */);
 
 /* Preliminary stage (Alg. 3: x_i = grad_i + e_i; send ||x_i||, receive the maximum; M = (t_p / sqrt(d)) * l,
@@ -138,6 +141,13 @@ int thc_compress(const thc_params* p, uint32_t worker_id, uint64_t round, const 
 int thc_compress_all(const thc_params* p, uint64_t round, const void* const* grads /* host */,
                      float* const* ef_inout /* host or NULL */, float* range_M, uint8_t* const* packed_out /* host */,
                      void* ws, void* stream);
+
+/* Status of the last single-launch sweep (thc_params.single_launch) that used this workspace: the first 32-bit word
+ * of the workspace, valid once the stream has been synchronized.  0 = fine.  1 = a workgroup waited in vain for
+ * another one (workgroups were not dispatched in the order and to the XCDs the sweep counts on): every wait in the
+ * kernel is bounded, nothing hangs, but that call's outputs are invalid and the caller should repeat it with
+ * single_launch = 0.  Never seen on MI355X; tests and bench.py assert it is 0. */
+enum { THC_SWEEP_OK = 0, THC_SWEEP_TIMEOUT = 1 };
 
 /* Main stage, PS side (Alg. 2: Y = sum_i T[Z_i]; the PS pseudocode's lookup + aggregate steps).
  *   packed    host array of n device pointers, each d*b/8 bytes.

@@ -23,7 +23,7 @@ class thc_params(C.Structure):
     _fields_ = [("d", C.c_uint64), ("block", C.c_uint64), ("n", C.c_uint32), ("b", C.c_uint32),
                 ("g", C.c_uint32), ("agg_bits", C.c_uint32), ("in_dtype", C.c_uint32), ("t_p", C.c_float),
                 ("seed", C.c_uint64), ("table", C.c_uint8 * 256), ("stage_order", C.c_uint32),
-                ("first_block", C.c_uint32), ("group_log2", C.c_uint32), ("reserved", C.c_uint32)]
+                ("first_block", C.c_uint32), ("group_log2", C.c_uint32), ("single_launch", C.c_uint32)]
 
 
 class ThcError(RuntimeError):
@@ -67,11 +67,12 @@ def lib():
 
 def make_params(d: int, block: int, n: int, b: int, g: int, t_p: float, seed: int, table: Sequence[int],
                 agg_bits: int = 8, in_dtype: int = THC_DTYPE_F32, stage_order: int = THC_ORDER_ASCENDING,
-                first_block: int = 0, group_log2: int = 0) -> thc_params:
+                first_block: int = 0, group_log2: int = 0, single_launch: int = 0) -> thc_params:
     p = thc_params()
     p.stage_order = stage_order
     p.first_block = first_block
     p.group_log2 = group_log2
+    p.single_launch = single_launch
     p.d, p.block, p.n, p.b, p.g = d, block, n, b, g
     p.agg_bits, p.in_dtype, p.t_p, p.seed = agg_bits, in_dtype, t_p, seed
     for i, v in enumerate(table):

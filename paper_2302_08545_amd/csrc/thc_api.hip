@@ -35,6 +35,7 @@ int validate(const thc_params* p) {
   if (!(p->t_p > 0.f) || !std::isfinite(p->t_p)) return THC_EINVAL;
   if (p->stage_order != THC_ORDER_ASCENDING && p->stage_order != THC_ORDER_SPLIT) return THC_EINVAL;
   if (p->group_log2 != 0 && (p->group_log2 < 10 || p->group_log2 > 40)) return THC_EINVAL;
+  if (p->single_launch > 1) return THC_EINVAL;
   const uint32_t top = (1u << p->b) - 1;
   if (p->table[0] != 0 || p->table[top] != p->g) return THC_ETABLE;
   for (uint32_t z = 0; z < top; ++z)
@@ -164,33 +165,29 @@ TileMap lo_tilemap(const Plan& pl, uint64_t len) {
 }
 
 // ---- workspace layout --------------------------------------------------------------------------------------
-// [0, 256)   status word of the last single-launch sweep (0 = fine), rest reserved
-// ring       the half-rotated vectors in flight: one group of blocks (launch-by-launch path) or a few block-sized
-//            slots per vector (single-launch path); ring_floats(p, ef) binary32 values
-// partials   n * (d >> min(L, 13)) binary64 partial sums of squares (one per 8192 coordinates, or per block)
-// sync       counters of the single-launch path, K * SYNC_PER_UNIT words
-// lut        device copy of the quantizer's grid-cell table, 256 words
+// [0, header)  status word of the last single-launch sweep (0 = fine), the rest reserved.  The header is 2 MiB
+//              (4 KiB for small rings) so that the ring is aligned like the workspace itself: the passes' tilings
+//              count on address bits up to 2^20.
+// ring         the half-rotated vectors in flight: one group of blocks (launch-by-launch path) or a few block-sized
+//              slots per vector (single-launch path); ring_floats(p, ef) binary32 values
+// partials     n * (d >> min(L, 13)) binary64 partial sums of squares (one per 8192 coordinates, or per block)
+// sync         counters of the single-launch path, K * SYNC_PER_UNIT words
+// lut          device copy of the quantizer's grid-cell table, 256 words
 //
 // Launch-by-launch path: a group is a run of whole blocks of every vector in the call, sized so that the group's
 // intermediate (all vectors of the call together) is about 2^group_log2 coordinates; the workspace does not grow
 // with d.  Random streams are indexed by global coordinate, so the grouping never changes a result.
-constexpr size_t WS_HEADER = 256;
-constexpr uint32_t DEFAULT_GROUP_LOG2 = 27;
+constexpr size_t WS_HEADER_BIG = 1u << 21, WS_HEADER_SMALL = 4096;
+constexpr uint32_t DEFAULT_GROUP_LOG2 = 29;
+constexpr uint32_t DEFAULT_GROUP_LOG2_SMALL = 25;   // with thc_params.single_launch: the caller is after a small workspace
 // From a unit's last first-pass workgroup being dispatched to its range being visible, the chip gets through about
 // this many workgroups (measured on the VGG16-shaped workload: trailing by fewer steps leaves consumers waiting,
 // by more pushes the ring out of the memory-side cache).  A unit's next phase trails by at least that.
 constexpr uint32_t LATENCY_WORKGROUPS = 1024;
 
-uint32_t latency_workgroups() {
-  if (const char* e = std::getenv("THC_PIPE_LATENCY_WG")) {   // tuning aid; any value gives the same results
-    const long v = std::strtol(e, nullptr, 10);
-    if (v >= 1 && v <= (1 << 20)) return (uint32_t)v;
-  }
-  return LATENCY_WORKGROUPS;
-}
-
 uint64_t group_coords(const thc_params* p, uint32_t W) {
-  const uint64_t target = 1ull << (p->group_log2 ? p->group_log2 : DEFAULT_GROUP_LOG2);
+  const uint64_t target =
+      1ull << (p->group_log2 ? p->group_log2 : p->single_launch ? DEFAULT_GROUP_LOG2_SMALL : DEFAULT_GROUP_LOG2);
   uint64_t gc = target / W / p->block * p->block;
   if (gc < p->block) gc = p->block;
   if (gc > p->d) gc = p->d;
@@ -198,7 +195,8 @@ uint64_t group_coords(const thc_params* p, uint32_t W) {
 }
 
 // Shape of the single-launch sweep over W vectors (thc_pipeline.hpp), or ok = false where it does not apply:
-// it takes the split stage order, blocks of 2^17 .. 2^22 coordinates, at least four blocks, and the default grouping.
+// it is asked for by thc_params.single_launch and takes the split stage order, blocks of 2^17 .. 2^22 coordinates,
+// at least four blocks, and the default grouping.
 struct PipeShape {
   bool ok;
   uint32_t nphase, lag, slots;
@@ -207,12 +205,12 @@ struct PipeShape {
 PipeShape pipe_shape(const thc_params* p, const Plan& pl, uint32_t W, bool ef) {
   PipeShape sh{};
   const uint64_t K = p->d / p->block;
-  sh.ok = pl.split && pl.nmid == 0 && pl.L >= 17 && K >= 4 && K <= 65536 && p->group_log2 == 0;
+  sh.ok = p->single_launch == 1 && pl.split && pl.nmid == 0 && pl.L >= 17 && K >= 4 && K <= 65536 && p->group_log2 == 0;
   sh.nphase = ef ? 4 : 2;
   // A consumer should find its producers finished and published: they are `lag` steps ahead, a step being
   // nphase * Tu workgroups.
   const uint64_t per_step = (uint64_t)sh.nphase * ((uint64_t)W << pl.R);
-  sh.lag = 1 + (uint32_t)((latency_workgroups() + per_step - 1) / per_step);
+  sh.lag = 1 + (uint32_t)((LATENCY_WORKGROUPS + per_step - 1) / per_step);
   sh.slots = (sh.nphase - 1) * sh.lag + 2;
   return sh;
 }
@@ -232,7 +230,7 @@ size_t partial_count(const thc_params* p, const Plan& pl) { return (size_t)p->n 
 
 size_t sync_words(const thc_params* p) {
   const uint64_t K = p->d / p->block;
-  return K <= 65536 ? (size_t)K * SYNC_PER_UNIT : 0;
+  return (p->single_launch == 1 && K <= 65536) ? (size_t)K * SYNC_PER_UNIT : 0;
 }
 
 struct WsLayout {
@@ -249,10 +247,11 @@ struct WsLayout {
 WsLayout ws_layout(void* ws, const thc_params* p, const Plan& pl, bool ef) {
   char* base = static_cast<char*>(ws);
   WsLayout w{};
-  size_t at = WS_HEADER;
+  const size_t ring_bytes = ring_floats(p, pl, ef) * sizeof(float);
+  size_t at = ring_bytes >= WS_HEADER_BIG ? WS_HEADER_BIG : WS_HEADER_SMALL;
   w.status = reinterpret_cast<uint32_t*>(base);
   w.ring = reinterpret_cast<float*>(base + at);
-  at += ring_floats(p, pl, ef) * sizeof(float);
+  at += ring_bytes;
   w.partials = reinterpret_cast<double*>(base + at);
   at += partial_count(p, pl) * sizeof(double);
   w.sync = reinterpret_cast<uint32_t*>(base + at);

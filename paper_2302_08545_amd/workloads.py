@@ -166,7 +166,7 @@ def moved_bytes_per_coord(w: Workload) -> float:
     """HBM bytes per (padded) coordinate the kernels actually move in one full round: every pass of a transform
     reads and writes the vector once (rocprofv3's FETCH_SIZE / WRITE_SIZE read exactly this on the VGG16-shaped
     workload).  A transform of 2^L coordinates takes the first pass (13 bits), the last pass (up to 9 bits) and,
-    above L = 22, ceil((L - 13) / 7) - 2 passes in between."""
+    above L = 22, ceil((L - 13) / 7) - 1 passes in between."""
     in_b = 4 if w.dtype == "f32" else 2
     L = w.block.bit_length() - 1
     mids = 0 if L - 13 <= 9 else -(-(L - 13) // 7) - 1

@@ -34,12 +34,12 @@ def table_for(b, g, p=1 / 32):
 
 
 def both_params(d, block, n, b=4, g=30, agg_bits=8, p=1 / 32, bf16=False, seed=SEED, table=None, order=0,
-                first_block=0, group_log2=0):
+                first_block=0, group_log2=0, single_launch=0):
     T = table if table is not None else table_for(b, g, p)
     tp = o.t_p_of(p)
     P = o.Params(d=d, block=block, n=n, b=b, g=g, t_p=tp, seed=seed, table=T, agg_bits=agg_bits, order=order)
     L = api.make_params(d, block, n, b, g, tp, seed, T, agg_bits, api.THC_DTYPE_BF16 if bf16 else api.THC_DTYPE_F32,
-                        order, first_block, group_log2)
+                        order, first_block, group_log2, single_launch)
     return P, L
 
 
@@ -477,13 +477,13 @@ def test_homomorphism_on_the_library_itself():
                                                        (18, 4, 1, True, True, 0), (19, 7, 2, False, True, 3),
                                                        (20, 4, 2, True, False, 1 << 13), (17, 9, 5, False, False, 0)])
 def test_single_launch_sweep_matches_the_oracle(L, K, n, ef, bf16, first_block):
-    """Split stage order, blocks of 2^17 and more, at least four blocks: thc_compress_all and thc_compress run all
-    passes of all blocks in one launch (blocks follow each other through a ring of slots, workgroups wait on
-    counters).  Range, packed bytes and error feedback must equal the oracle's and the launch-by-launch path's,
+    """thc_params.single_launch with the split stage order, blocks of 2^17 and more, at least four blocks:
+    thc_compress_all and thc_compress run all passes of all blocks in one launch (blocks follow each other through a
+    ring of slots, workgroups wait on counters).  Range, packed bytes and error feedback must equal the oracle's and the launch-by-launch path's,
     and the status word must stay 0 (no wait timed out, no workgroup ran on an unexpected XCD)."""
     block = 1 << L
     d, j0 = block * K, first_block * block
-    P, Lp = both_params(d, block, n, bf16=bf16, order=1, first_block=first_block)
+    P, Lp = both_params(d, block, n, bf16=bf16, order=1, first_block=first_block, single_launch=1)
     R = GpuRound(Lp, ef=ef)
     grads = make_grads(d, n, seed=L + K, bf16=bf16)
     for x in grads:
@@ -522,7 +522,7 @@ def test_single_launch_sweep_matches_the_oracle(L, K, n, ef, bf16, first_block):
             assert_indices_match(R.packed[i].cpu().numpy(), pk, 4, f"round {rnd} worker {i} alone")
             if ef:
                 assert rel_l2(R.efs[i].cpu().numpy(), ne) <= 1e-5
-        # and the launch-by-launch path (an explicit group size switches the single launch off): bit for bit
+        # and the launch-by-launch path, two blocks to a group: bit for bit
         _, Lg = both_params(d, block, n, bf16=bf16, order=1, first_block=first_block, group_log2=L + 1)
         G = GpuRound(Lg, ef=ef)
         if ef:
@@ -778,7 +778,7 @@ def checksum64(t):
     return int(t.view(torch.int64).sum().cpu()) & 0xFFFFFFFFFFFFFFFF
 
 
-def _launch_shape_parity(w, blocks, workers=None, rounds=1, order=1, alone=None):
+def _launch_shape_parity(w, blocks, workers=None, rounds=1, order=1, alone=None, single_launch=0):
     """A workload at the size and in the launch configuration bench.py times it in (thc_compress_all, thc_aggregate,
     thc_decompress on the whole vectors).  The oracle checks the sampled blocks (blocks are independent THC
     instances) for the sampled workers, working from the very range the GPU used, which itself must be within 2^-23
@@ -791,7 +791,7 @@ def _launch_shape_parity(w, blocks, workers=None, rounds=1, order=1, alone=None)
     B = w.block
     P_blk = o.Params(d=B, block=B, n=w.n, b=w.b, g=w.g, t_p=tp, seed=SEED, table=T, agg_bits=w.agg_bits, order=order)
     L = api.make_params(w.d, B, w.n, w.b, w.g, tp, SEED, T, w.agg_bits,
-                        api.THC_DTYPE_BF16 if w.dtype == "bf16" else api.THC_DTYPE_F32, order)
+                        api.THC_DTYPE_BF16 if w.dtype == "bf16" else api.THC_DTYPE_F32, order, 0, 0, single_launch)
     grads = [wl.gradient(w, i, device=DEV) for i in range(w.n)]
     for i in (0, w.n - 1):
         print(f"{w.name} input {i}: {wl.checksum(grads[i][:1 << 24])}")
@@ -853,14 +853,15 @@ def _need_memory(gib):
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("order", [1, 0], ids=["split-order", "ascending-order"])
-def test_vgg16_shape_full_size_sampled_blocks(order):
-    """The 138M-coordinate / 2^28-padded, 8-worker, b=4 configuration (bench.py's default; it runs the split order)."""
+@pytest.mark.parametrize("order,single", [(1, 0), (0, 0), (1, 1)], ids=["split-order", "ascending-order", "single-launch"])
+def test_vgg16_shape_full_size_sampled_blocks(order, single):
+    """The 138M-coordinate / 2^28-padded, 8-worker, b=4 configuration (bench.py's default: the split order, launch by
+    launch; bench.py --single-launch is the third case)."""
     w = wl.C3
     _need_memory(16)
     first_pad = (w.real + w.block - 1) // w.block          # blocks from here on are all zero
     blocks = (0, 14, 63, 131, first_pad - 1)               # conv part, FC part, the partly padded block
-    R, _ = _launch_shape_parity(w, blocks, order=order, alone=5 if order == 1 else None)
+    R, _ = _launch_shape_parity(w, blocks, order=order, alone=5 if order == 1 else None, single_launch=single)
     M_gpu = R.range_M.cpu().numpy()
     assert np.all(M_gpu[first_pad:] == 0) and np.all(M_gpu[:first_pad] > 0)
     assert float(R.out[first_pad * w.block:].abs().max()) == 0.0
@@ -885,11 +886,12 @@ def test_bert_large_shape_full_size_sampled_blocks(w):
 
 
 @pytest.mark.timeout(900)
-def test_gpt2_xl_shape_prefix_all_workers():
+@pytest.mark.parametrize("single", [0, 1], ids=["launch-by-launch", "single-launch"])
+def test_gpt2_xl_shape_prefix_all_workers(single):
     """The first 48 blocks of 2^22 of the GPT-2-XL-shaped workload (what bench.py --workload c5_gpt2_xl --blocks 48
     runs): 32 workers, bf16 gradients, error feedback, two rounds; the oracle follows three workers."""
     _need_memory(70)
-    _launch_shape_parity(wl.shrink(wl.C5, 48), (0, 47), workers=[0, 13, 31], rounds=2)
+    _launch_shape_parity(wl.shrink(wl.C5, 48), (0, 47), workers=[0, 13, 31], rounds=2, single_launch=single)
 
 
 # ----------------------------------------------------------------------------- the other workload recipes

@@ -64,18 +64,21 @@ def test_workspace_size():
     p = _p()
     # a ring that holds one group of blocks of all n workers + one double per min(B, 8192) coordinates per worker
     assert api.thc_workspace_bytes(p) >= 4 * (1 << 12) * 4 + 4 * 4 * 8
-    # it does not grow with d: the 2^28 vector of the VGG16-shaped workload takes a ring of 2^27 values (one group of
-    # the launch-by-launch path; the single-launch sweep needs four slots of 8 * 2^20), not n * d
+    # it does not grow with d: the 2^28 vector of the VGG16-shaped workload takes a ring of 2^29 values (one group of
+    # blocks of all workers), not n * d = 2^31
     big = _p(d=1 << 28, block=1 << 20, n=8)
-    assert (1 << 27) * 4 <= api.thc_workspace_bytes(big) < (1 << 27) * 4 * 1.02
+    assert (1 << 29) * 4 <= api.thc_workspace_bytes(big) < (1 << 29) * 4 * 1.02
+    assert api.thc_workspace_bytes(_p(d=1 << 30, block=1 << 20, n=8)) < (1 << 29) * 4 * 1.05
     small = _p(d=1 << 28, block=1 << 20, n=8, group_log2=22)
     assert api.thc_workspace_bytes(small) < api.thc_workspace_bytes(big) / 3
-    # error feedback adds two phases to the single-launch sweep, hence slots to its ring: 32 workers with 2^22 blocks
-    # in the split stage order take 8 slots of n * block instead of 4
-    wide = dict(d=372 << 22, block=1 << 22, n=32, agg_bits=16, stage_order=1)
+    # the single-launch sweep takes a ring of a few block-sized slots per worker: 4 without, 8 with error feedback
+    # (two more phases follow each block), e.g. 32 workers with 2^22 blocks
+    wide = dict(d=372 << 22, block=1 << 22, n=32, agg_bits=16, stage_order=1, single_launch=1, group_log2=0)
     no_ef, with_ef = api.thc_workspace_bytes(_p(**wide), False), api.thc_workspace_bytes(_p(**wide), True)
     assert 4 * 32 * (1 << 22) * 4 <= no_ef < 4 * 32 * (1 << 22) * 4 * 1.05
     assert 8 * 32 * (1 << 22) * 4 <= with_ef < 8 * 32 * (1 << 22) * 4 * 1.05
+    sweep = _p(d=1 << 28, block=1 << 20, n=8, stage_order=1, single_launch=1)
+    assert 4 * 8 * (1 << 20) * 4 <= api.thc_workspace_bytes(sweep) < api.thc_workspace_bytes(big)
     # the uniform variant with rotation keeps all n rotated vectors
     u = api.make_params(1 << 20, 1 << 12, 4, 4, 15, 2.0, 7, list(range(16)), 8)
     assert api.thc_uniform_workspace_bytes(u, True) >= 4 * (1 << 20) * 4
@@ -104,6 +107,7 @@ def test_workspace_size():
     (dict(stage_order=2), -1),
     (dict(group_log2=9), -1),
     (dict(group_log2=41), -1),
+    (dict(single_launch=2), -1),
 ])
 def test_validation_codes(kw, code):
     p = _p(**kw)
