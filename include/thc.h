@@ -161,6 +161,15 @@ int thc_aggregate(const thc_params* p, const uint8_t* const* packed /* host */, 
 int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const float* range_M,
                    float* out, void* ws, void* stream);
 
+/* thc_decompress for callers that cannot allocate device memory and bring no workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same computation, bit for bit, with the
+ * intermediate in a 32 MB scratch array that is part of the library's code object (one per GPU, held until the
+ * process ends).  The call allocates nothing and frees nothing.  Blocks of at most 2^23 coordinates (else
+ * THC_EUNSUPPORTED); d is unlimited (the vector goes through the scratch array in groups of whole blocks).
+ * Every call on a GPU uses that GPU's one array: calls that overlap on the same GPU (different streams) race. */
+int thc_decompress_noalloc(const thc_params* p, uint64_t round, const void* agg, const float* range_M, float* out,
+                           void* stream);
+
 /* ---- Uniform THC (Alg. 1; Sec. 4.2 "Homomorphic USQ") -----------------------------------------------
  * The simplified variant the paper generalises: 2^b uniformly spaced quantization values on the GLOBAL
  * range [m, M] = [min_i min(x_i), max_i max(x_i)] (per block), no lookup table.  `p` must carry the identity

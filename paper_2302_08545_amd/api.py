@@ -14,7 +14,8 @@ THC_DTYPE_F32, THC_DTYPE_BF16 = 0, 1
 THC_ORDER_ASCENDING, THC_ORDER_SPLIT = 0, 1
 
 EXPORTS = ("thc_version", "thc_strerror", "thc_workspace_bytes", "thc_prepare_range", "thc_compress",
-           "thc_compress_all", "thc_aggregate", "thc_decompress", "thc_uniform_workspace_bytes",
+           "thc_compress_all", "thc_aggregate", "thc_decompress", "thc_decompress_noalloc",
+           "thc_uniform_workspace_bytes",
            "thc_uniform_prepare_range", "thc_uniform_compress", "thc_uniform_decompress", "thc_threshold",
            "thc_solve_table", "thc_solve_table_bruteforce", "thc_describe_plan")
 
@@ -52,6 +53,7 @@ def lib():
         L.thc_compress_all.argtypes = [pp, u64, C.POINTER(vp), C.POINTER(vp), vp, C.POINTER(vp), vp, vp]
         L.thc_aggregate.argtypes = [pp, C.POINTER(vp), vp, vp]
         L.thc_decompress.argtypes = [pp, u64, vp, vp, vp, vp, vp]
+        L.thc_decompress_noalloc.argtypes = [pp, u64, vp, vp, vp, vp]
         L.thc_uniform_prepare_range.argtypes = [pp, u64, C.POINTER(vp), C.POINTER(vp), C.c_int, vp, vp, vp, vp]
         L.thc_uniform_compress.argtypes = [pp, u32, u64, vp, vp, C.c_int, vp, vp, vp, vp, vp]
         L.thc_uniform_decompress.argtypes = [pp, u64, vp, C.c_int, vp, vp, vp, vp, vp]
@@ -148,6 +150,11 @@ def thc_aggregate(p: thc_params, packed, agg_out, stream=None) -> None:
 def thc_decompress(p: thc_params, rnd: int, agg, range_M, out, ws, stream=None) -> None:
     _check(lib().thc_decompress(C.byref(p), rnd, _ptr(agg), _ptr(range_M), _ptr(out), _ptr(ws), _stream(stream)),
            "thc_decompress")
+
+
+def thc_decompress_noalloc(p: thc_params, rnd: int, agg, range_M, out, stream=None) -> None:
+    _check(lib().thc_decompress_noalloc(C.byref(p), rnd, _ptr(agg), _ptr(range_M), _ptr(out), _stream(stream)),
+           "thc_decompress_noalloc")
 
 
 def thc_uniform_prepare_range(p: thc_params, rnd: int, grads, ef, rotate: bool, range_m, range_M, ws,

@@ -589,6 +589,31 @@ void run_forward(const Forward& f) {
   }
 }
 
+// ---- scratch of the entry point that allocates nothing -------------------------------------------------------
+// One array per GPU the library's code object is loaded on, held until the process ends.  Its name is a host-side
+// stand-in: the device address comes from hipGetSymbolAddress, once per device, with that device current.
+constexpr uint64_t STATIC_SCRATCH_FLOATS = 1ull << 23;   // 32 MB
+static __device__ __align__(256) float g_static_scratch[STATIC_SCRATCH_FLOATS];
+
+constexpr int MAX_DEVICES = 64;
+float* g_scratch_ptr[MAX_DEVICES] = {};
+
+int static_scratch(float** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return THC_ELAUNCH;
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_scratch));
+    if (e != hipSuccess || !ptr) {
+      std::fprintf(stderr, "libthc: hipGetSymbolAddress failed: %s\n", hipGetErrorString(e));
+      return THC_ELAUNCH;
+    }
+    g_scratch_ptr[dev] = static_cast<float*>(ptr);
+  }
+  *out = g_scratch_ptr[dev];
+  return THC_OK;
+}
+
 const char* const kNames[] = {"THC_OK", "THC_EINVAL", "THC_ETABLE", "THC_EOVERFLOW", "THC_EUNSUPPORTED", "THC_ELAUNCH"};
 
 }  // namespace
@@ -762,15 +787,11 @@ int thc_aggregate(const thc_params* p, const uint8_t* const* packed, void* agg_o
   return check_launch();
 }
 
-int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const float* range_M, float* out,
-                   void* ws, void* stream) {
-  const int rc = validate(p);
-  if (rc) return rc;
-  if (round >> 32 || !agg || !range_M || !out || !ws) return THC_EINVAL;
-  if (!aligned16(agg) || !aligned16(out) || !aligned16(ws)) return THC_EINVAL;
-  const Plan pl = make_plan(p->block, p->stage_order);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  float* const slot = ws_layout(ws, p, pl, false).ring;
+namespace {
+
+// m + (Y/n)(M-m)/g and the inverse RHT, group by group through `slot` (room for `gc` coordinates, whole blocks)
+void run_decompress(const thc_params* p, const Plan& pl, uint64_t round, const void* agg, const float* range_M,
+                    float* out, float* slot, uint64_t gc, hipStream_t s) {
   InvLoArgs lo{};
   lo.L = (uint32_t)pl.L;
   lo.src_bits = p->agg_bits;
@@ -781,7 +802,6 @@ int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const f
   hi.k0 = (uint32_t)p->seed;
   hi.k1 = (uint32_t)(p->seed >> 32);
   hi.mode = 0;
-  const uint64_t gc = group_coords(p, 1);
   for (uint64_t x0 = 0; x0 < p->d; x0 += gc) {
     const uint64_t len = p->d - x0 < gc ? p->d - x0 : gc;
     lo.src.p[0] = static_cast<const uint8_t*>(agg) + x0 / 8 * p->agg_bits;
@@ -790,6 +810,40 @@ int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const f
     hi.j0 = base_coord(p) + x0;
     run_inverse(p, pl, lo, slot, hi, len, 1, s);
   }
+}
+
+}  // namespace
+
+int thc_decompress(const thc_params* p, uint64_t round, const void* agg, const float* range_M, float* out,
+                   void* ws, void* stream) {
+  const int rc = validate(p);
+  if (rc) return rc;
+  if (round >> 32 || !agg || !range_M || !out || !ws) return THC_EINVAL;
+  if (!aligned16(agg) || !aligned16(out) || !aligned16(ws)) return THC_EINVAL;
+  const Plan pl = make_plan(p->block, p->stage_order);
+  run_decompress(p, pl, round, agg, range_M, out, ws_layout(ws, p, pl, false).ring, group_coords(p, 1),
+                 static_cast<hipStream_t>(stream));
+  return check_launch();
+}
+
+int thc_decompress_noalloc(const thc_params* p, uint64_t round, const void* agg, const float* range_M, float* out,
+                           void* stream) {
+  const int rc = validate(p);
+  if (rc) return rc;
+  if (round >> 32 || !agg || !range_M || !out) return THC_EINVAL;
+  if (!aligned16(agg) || !aligned16(out)) return THC_EINVAL;
+  if (p->block > STATIC_SCRATCH_FLOATS) {
+    std::fprintf(stderr, "libthc: thc_decompress_noalloc takes blocks of at most %llu coordinates (got %llu)\n",
+                 (unsigned long long)STATIC_SCRATCH_FLOATS, (unsigned long long)p->block);
+    return THC_EUNSUPPORTED;
+  }
+  float* scratch = nullptr;
+  const int rs = static_scratch(&scratch);
+  if (rs) return rs;
+  const Plan pl = make_plan(p->block, p->stage_order);
+  uint64_t gc = STATIC_SCRATCH_FLOATS / p->block * p->block;   // whole blocks that fit the scratch array
+  if (gc > p->d) gc = p->d;
+  run_decompress(p, pl, round, agg, range_M, out, scratch, gc, static_cast<hipStream_t>(stream));
   return check_launch();
 }
 
