@@ -226,8 +226,8 @@ double thc_threshold(double p);
  * table_out (host) and the attained cost (in units of sigma^2) to cost_out if not NULL. */
 int thc_solve_table(uint32_t b, uint32_t g, double p, uint8_t* table_out /* host */, double* cost_out /* host */);
 
-/* The same optimum by exhaustive search: every strictly increasing table from 0 to g is visited with the
- * stars-and-bars enumeration of App. B (Alg. 4) and scored with the closed-form objective.  A cross-check of
+/* The same optimum by exhaustive search: every strictly increasing table from 0 to g (the candidates App. B
+ * counts; here walked as combinations of the interior values) is scored with the closed-form objective.  A cross-check of
  * thc_solve_table for small (b, g); returns THC_EUNSUPPORTED when more than 4e9 candidates would have to be
  * visited.  count_out (may be NULL) receives the number of candidates, C(g-1, 2^b-2). */
 int thc_solve_table_bruteforce(uint32_t b, uint32_t g, double p, uint8_t* table_out /* host */,

@@ -84,8 +84,8 @@ int thc_solve_table_bruteforce(uint32_t b, uint32_t g, double p, uint8_t* table_
                                uint64_t* count_out) {
   if (!table_out || b < 1 || b > 8 || g > 255 || g < (1u << b) - 1 || !(p > 0.0 && p < 1.0)) return THC_EINVAL;
   const int k = (1 << b) - 1;              // bins = gaps between consecutive table values, each >= 1
-  const int balls = (int)g - k;            // spare units to distribute (App. B, stars and bars)
-  // C(balls + k - 1, k - 1) candidates; refuse searches that would not end in reasonable time
+  const int balls = (int)g - k;            // spare units beyond the k unit gaps
+  // C(balls + k - 1, k - 1) = C(g - 1, k - 1) candidates; refuse searches that would not end in reasonable time
   long double cnt = 1.0L;
   for (int i = 1; i <= k - 1; ++i) cnt = cnt * (balls + i) / i;
   if (cnt > 4.0e9L) return THC_EUNSUPPORTED;
@@ -103,19 +103,21 @@ int thc_solve_table_bruteforce(uint32_t b, uint32_t g, double p, uint8_t* table_
       const double m0 = Phi[j] - Phi[i], m1 = -(phi[j] - phi[i]), m2 = m0 - (q[j] * phi[j] - q[i] * phi[i]);
       edge[(size_t)i * (G + 1) + j] = -m2 + (q[i] + q[j]) * m1 - q[i] * q[j] * m0;
     }
-  // Alg. 4: start with all balls in bin 0; then repeatedly take the first non-empty bin a, move one of its
-  // balls to bin a+1 and put the rest back into bin 0.
-  std::vector<int> B(k, 0), best(k + 1, 0), cur(k + 1, 0);
-  B[0] = balls;
+  // A strictly increasing table from 0 to g is a choice of its k - 1 interior values out of 1 .. g-1.  The choices are
+  // walked in lexicographic order (the next combination: bump the rightmost value that still has room, reset what
+  // follows it to the smallest values allowed), carrying the cost of the unchanged prefix along.  Only completeness
+  // matters to an exhaustive search; the count C(g-1, k-1) is returned for the caller to check.
+  const int m = k - 1;                                   // interior values cur[1 .. m]; cur[0] = 0, cur[k] = g
+  std::vector<int> best(k + 1, 0), cur(k + 1, 0);
+  std::vector<double> prefix(k + 1, 0.0);                // prefix[i] = cost of the pairs (cur[0],cur[1]) .. (cur[i-1],cur[i])
+  cur[k] = G;
+  for (int i = 1; i <= m; ++i) cur[i] = i;
   double best_cost = HUGE_VAL;
   uint64_t visited = 0;
+  int from = 1;                                          // first position whose prefix cost has to be refreshed
   for (;;) {
-    cur[0] = 0;
-    double c = 0.0;
-    for (int i = 0; i < k; ++i) {
-      cur[i + 1] = cur[i] + 1 + B[i];
-      c += edge[(size_t)cur[i] * (G + 1) + cur[i + 1]];
-    }
+    for (int i = from; i <= k; ++i) prefix[i] = prefix[i - 1] + edge[(size_t)cur[i - 1] * (G + 1) + cur[i]];
+    const double c = prefix[k];
     ++visited;
     bool take = visited == 1;
     if (!take) {
@@ -125,13 +127,12 @@ int thc_solve_table_bruteforce(uint32_t b, uint32_t g, double p, uint8_t* table_
         take = std::lexicographical_compare(cur.begin(), cur.end(), best.begin(), best.end());
     }
     if (take) { best = cur; best_cost = c; }
-    int a = 0;
-    while (a < k && B[a] == 0) ++a;
-    if (a >= k - 1) break;                  // all balls sit in the last bin (or there are none): enumeration complete
-    const int rest = B[a] - 1;
-    B[a + 1] += 1;
-    B[a] = 0;
-    B[0] = rest;
+    int i = m;
+    while (i >= 1 && cur[i] == G - 1 - (m - i)) --i;     // position i can grow while the values after it still fit
+    if (i < 1) break;
+    ++cur[i];
+    for (int j = i + 1; j <= m; ++j) cur[j] = cur[j - 1] + 1;
+    from = i;
   }
   for (int i = 0; i <= k; ++i) table_out[i] = (uint8_t)best[i];
   if (cost_out) *cost_out = best_cost;
