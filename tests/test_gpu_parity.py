@@ -847,6 +847,9 @@ def _launch_shape_parity(w, blocks, workers=None, rounds=1, order=1, alone=None,
 
 
 def _need_memory(gib):
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info()
     if free < gib * (1 << 30):
         pytest.skip(f"needs about {gib} GiB of device memory")
@@ -892,6 +895,17 @@ def test_gpt2_xl_shape_prefix_all_workers(single):
     runs): 32 workers, bf16 gradients, error feedback, two rounds; the oracle follows three workers."""
     _need_memory(70)
     _launch_shape_parity(wl.shrink(wl.C5, 48), (0, 47), workers=[0, 13, 31], rounds=2, single_launch=single)
+
+
+@pytest.mark.timeout(1500)
+def test_gpt2_xl_shape_full_length_24_workers():
+    """The GPT-2-XL-shaped workload at its full length (1,557,611,200 coordinates, 372 blocks of 2^22, bf16, error
+    feedback).  With the 32 workers the configuration names, the buffers alone take 334 GB, more than the GPU has; 24
+    workers (255 GB with a 2 GB workspace) are what fits, and the length is never cut.  Two rounds; the oracle follows
+    two workers on three blocks, the last one partly padding."""
+    _need_memory(262)
+    w = wl.replace(wl.C5, n=24, name="c5_gpt2_xl_n24")
+    _launch_shape_parity(w, (0, 200, 371), workers=[0, 23], rounds=2)
 
 
 # ----------------------------------------------------------------------------- the other workload recipes
