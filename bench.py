@@ -24,8 +24,8 @@ CPU_SHARE = 16             # host cores that go with one GPU of the box
 
 def measured_traffic(workload_name):
     """Bytes the forward sweep moves between the L2s and memory per launch, from the tracked rocprofv3 counter
-    summary (profiles/forward_sweep_<workload>_hbm_bytes.txt, line `traffic_bytes_per_launch: N`), or None."""
-    path = os.path.join(ROOT, "profiles", f"forward_sweep_{workload_name}_hbm_bytes.txt")
+    summary (profiles/all_kernels_<workload>.txt, line `traffic_bytes_per_launch: N`), or None."""
+    path = os.path.join(ROOT, "profiles", f"all_kernels_{workload_name}.txt")
     try:
         m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
         return float(m.group(1)) if m else None
@@ -293,6 +293,13 @@ def main():
                      "algorithmic_bytes": fwd_alg_bytes, "launch_ms": fwd_ms,
                      "traffic": measured_traffic(w.name) if default_config else None},
     }
+    if w.name == "c3_vgg16" and default_config:
+        # Vector-ALU view of the same sweep: wave64 instructions it issues (rocprofv3 SQ_INSTS_VALU,
+        # profiles/sq_counters_c3_vgg16.txt) against what 1024 SIMDs issue at one instruction per 4 cycles, 2.35 GHz
+        insts = 4 * (242089984 + 231800832)
+        result["alu_roofline"] = {"bound": "alu", "kernel": result["roofline"]["kernel"], "unit": "wave64 instructions/s",
+                                  "achieved": insts / (fwd_ms * 1e-3), "peak": 1024 * 2.35e9 / 4,
+                                  "frac": insts / (fwd_ms * 1e-3) / (1024 * 2.35e9 / 4)}
     if uniform:
         # Alg. 1 runs other kernels: the figures above that describe Alg. 3's passes do not apply
         for key in ("roofline", "moved_bytes_per_coord", "moved_GBps"):
