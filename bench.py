@@ -247,6 +247,7 @@ def main():
     per_step = dt / args.steps
     stage_ms = {name: sum(ev[k].elapsed_time(ev[k + 1]) for ev in events) / len(events)
                 for k, name in enumerate(stage_names)}
+    rounds_ms = sorted(ev[0].elapsed_time(ev[4]) for ev in events)   # each round by its own events
     bpc = wl.bytes_per_coord(w)
     in_bytes = 4 if w.dtype == "f32" else 2
     # Dominant launch: the forward sweep, thc_compress_all (one kernel launch that takes all workers' blocks through
@@ -267,6 +268,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": per_step * 1e3,
+        "ms_per_step_median": rounds_ms[len(rounds_ms) // 2],
+        "ms_per_step_min": rounds_ms[0],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,

@@ -310,7 +310,7 @@ __device__ __forceinline__ void hi_front(const float* src, const HiGeom<R>& g, f
 // Two groups of eight consecutive coordinates per thread, with the last row bit (if any) applied:
 // tile index of each group in idx[], values in v[][].
 template <int R>
-__device__ __forceinline__ void hi_back(const float* lds, int t, int (&idx)[2], float (&v)[2][8]) {
+__device__ __forceinline__ void hi_back_index(int t, int (&idx)[2]) {
   using S = HiSplit<R>;
   if constexpr (S::NB2 == 1) {
     const int oct = t & (S::W / 8 - 1), r = t >> (S::LOGW - 3);      // r < 2^(R-1)
@@ -320,6 +320,12 @@ __device__ __forceinline__ void hi_back(const float* lds, int t, int (&idx)[2], 
     idx[0] = 8 * t;
     idx[1] = 8 * (t + NT);
   }
+}
+
+template <int R>
+__device__ __forceinline__ void hi_back(const float* lds, int t, int (&idx)[2], float (&v)[2][8]) {
+  using S = HiSplit<R>;
+  hi_back_index<R>(t, idx);
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const float4 p0 = *reinterpret_cast<const float4*>(&lds[idx[h]]);

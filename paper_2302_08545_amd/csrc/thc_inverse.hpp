@@ -226,20 +226,29 @@ struct InvHiArgs {
   float c;
 };
 
+// scale by 1/sqrt(B) and apply the diagonal; mode 1: (x + e) - that
 template <class A>
-__device__ __forceinline__ float4 inv_finish4(float4 v, uint32_t bits, const A& a, const float* out,
-                                              const void* grad, uint64_t j) {
+__device__ __forceinline__ float4 inv_finish4(float4 v, uint32_t bits, const A& a, float4 x, float4 e) {
   v.x = flip(v.x * a.c, bits & 1u);
   v.y = flip(v.y * a.c, (bits >> 1) & 1u);
   v.z = flip(v.z * a.c, (bits >> 2) & 1u);
   v.w = flip(v.w * a.c, (bits >> 3) & 1u);
   if (a.mode == 1) {
-    float4 x = a.bf16 ? load_grad4<true>(grad, j) : load_grad4<false>(grad, j);
-    const float4 e = *reinterpret_cast<const float4*>(out + j);
     x.x += e.x; x.y += e.y; x.z += e.z; x.w += e.w;
     v = make_float4(x.x - v.x, x.y - v.y, x.z - v.z, x.w - v.w);
   }
   return v;
+}
+
+template <class A>
+__device__ __forceinline__ float4 inv_finish4(float4 v, uint32_t bits, const A& a, const float* out,
+                                              const void* grad, uint64_t j) {
+  float4 x = make_float4(0.f, 0.f, 0.f, 0.f), e = x;
+  if (a.mode == 1) {
+    x = a.bf16 ? load_grad4<true>(grad, j) : load_grad4<false>(grad, j);
+    e = *reinterpret_cast<const float4*>(out + j);
+  }
+  return inv_finish4(v, bits, a, x, e);
 }
 
 struct alignas(16) SmemInvHi {
@@ -260,7 +269,9 @@ __device__ __forceinline__ void inv_hi_tile(const A& a, uint32_t tile, uint32_t 
   const void* const grad = a.grad.p[vec];
 
   if constexpr (R >= 2) {
-    hi_front<R>(xv, g, lds, t);
+    float4 x[4];
+    hi_issue_loads<R>(xv, g, t, x);
+    // the diagonal's bits while the loads travel
     // 32 consecutive tile indices are 32 consecutive coordinates, or, with 16-wide rows, two aligned halves
     if (t < TILE / 32) {
       if constexpr (HiGeom<R>::W >= 32) {
@@ -272,7 +283,28 @@ __device__ __forceinline__ void inv_hi_tile(const A& a, uint32_t tile, uint32_t 
         sgn[t] = (lo & 0xFFFFu) | (hi << 16);
       }
     }
+    hi_r0_to_lds<R>(x, lds, t);
+    hi_round1<R>(lds, t);
     int idx[2];
+    hi_back_index<R>(t, idx);
+    // error-feedback update: the gradient and the buffer's old contents are requested for both halves before
+    // anything is stored (the stores go to that same buffer), and while the tile's last stage runs
+    float4 gx[2][2], ex[2][2];
+    if (a.mode == 1) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const uint64_t j = g.coord(idx[h]);
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+          gx[h][k] = a.bf16 ? load_grad4<true>(grad, j + 4 * k) : load_grad4<false>(grad, j + 4 * k);
+          ex[h][k] = *reinterpret_cast<const float4*>(out + j + 4 * k);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+        for (int k = 0; k < 2; ++k) gx[h][k] = ex[h][k] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
     float v[2][8];
     hi_back<R>(lds, t, idx, v);
     __syncthreads();
@@ -280,8 +312,8 @@ __device__ __forceinline__ void inv_hi_tile(const A& a, uint32_t tile, uint32_t 
     for (int h = 0; h < 2; ++h) {
       const uint64_t j = g.coord(idx[h]);
       const uint32_t bits = sgn[idx[h] >> 5] >> (idx[h] & 31);
-      const float4 o0 = inv_finish4(make_float4(v[h][0], v[h][1], v[h][2], v[h][3]), bits, a, out, grad, j);
-      const float4 o1 = inv_finish4(make_float4(v[h][4], v[h][5], v[h][6], v[h][7]), bits >> 4, a, out, grad, j + 4);
+      const float4 o0 = inv_finish4(make_float4(v[h][0], v[h][1], v[h][2], v[h][3]), bits, a, gx[h][0], ex[h][0]);
+      const float4 o1 = inv_finish4(make_float4(v[h][4], v[h][5], v[h][6], v[h][7]), bits >> 4, a, gx[h][1], ex[h][1]);
       *reinterpret_cast<float4*>(out + j) = o0;
       *reinterpret_cast<float4*>(out + j + 4) = o1;
     }
