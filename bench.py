@@ -290,7 +290,10 @@ def main():
         "moved_GBps": wl.moved_bytes_per_coord(w) * w.d / per_step / 1e9,
         "stage_ms": stage_ms,
         "roofline": {"bound": "hbm", "kernel": ("k_pipe_forward (thc_compress_all, single launch)" if args.single_launch else
-                                "thc_compress_all: k_fwd_lo + k_range + k_fwd_hi_quant per group of blocks")
+                                "thc_compress_all: k_fwd_lo + k_range" + (" + k_mid" if w.block > 1 << 22 else "")
+                                + " + k_fwd_hi_quant" + (" + k_inv_lo" + (" + k_mid" if w.block > 1 << 22 else "")
+                                                         + " + k_inv_hi (error feedback)" if w.ef else "")
+                                + " per group of blocks")
                      if args.calls == "all" else "thc_prepare_range + n x thc_compress", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "algorithmic_bytes": fwd_alg_bytes, "launch_ms": fwd_ms,
