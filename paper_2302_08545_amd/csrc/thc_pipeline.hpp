@@ -3,10 +3,12 @@
 // optional error-feedback update).
 //
 // Why.  A 2^20-point block (4 MB) does not fit one compute unit, so its transform takes two trips through memory
-// with an intermediate in between.  Launch by launch that intermediate is as long as the vectors and travels to HBM
-// and back.  Here a block's intermediate is read back a few hundred microseconds after it was written, from a ring
-// of a few block-sized slots that stays in the 256 MB memory-side cache, and the memory-bound first pass of one
-// block shares the compute units with the ALU-bound quantizer of another.
+// with an intermediate in between.  Launch by launch that intermediate is as long as a group of blocks of all vectors
+// (gigabytes).  Here a block's intermediate is read back a few hundred microseconds after it was written, from a ring
+// of a few block-sized slots, and the memory-bound first pass of one block shares the compute units with the
+// ALU-bound quantizer of another.  Measured on MI355X the sweep takes the same time either way (within 2 %: both
+// forms run at what the fabric between the XCDs and memory delivers); what this form saves is workspace, a ring of
+// 4 (8 with error feedback) blocks per vector instead of a group's worth.
 //
 // Order.  Work items are numbered so that everything an item waits for has a smaller number:
 //   step s = 0, 1, ...:  [range item of unit s-1]  then, interleaved in groups of eight workgroups,
