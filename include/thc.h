@@ -94,8 +94,10 @@ typedef struct thc_params {
                           (which therefore does not grow with d); never a result */
   uint32_t single_launch; /* 0 or 1.  1: thc_compress and thc_compress_all run all passes of all blocks in ONE kernel
                           launch where they can (split stage order, blocks of 2^17 .. 2^22, at least four blocks,
-                          group_log2 = 0), blocks following each other through a ring of a few block-sized slots: an
-                          eighth of the workspace at about the same speed.  Never a result.  See thc_sweep_status */
+                          group_log2 = 0), blocks following each other through a ring of a few block-sized slots: a
+                          sixteenth of the workspace at the same speed (within 2 %) without error feedback; with error
+                          feedback and n * block beyond the 256 MB memory-side cache it is slower (n = 32, blocks of
+                          2^22: 81 against 46 ms).  Never a result.  See THC_SWEEP_OK below */
 } thc_params;
 
 /* Library version (major*10000 + minor*100 + patch). */
