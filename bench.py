@@ -33,6 +33,21 @@ def measured_traffic(workload_name):
         return None
 
 
+def profiled_kernel(workload_name, prefix):
+    """(kernel name, launches per round, average microseconds per launch) of the first kernel whose name starts with
+    `prefix` in the tracked rocprofv3 summary of the workload, or None."""
+    path = os.path.join(ROOT, "profiles", f"all_kernels_{workload_name}.txt")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    rounds = re.search(r"time over (\d+) rounds", text)
+    m = re.search(r"^(" + re.escape(prefix) + r".*?\))\s+(\d+)\s+([0-9.]+)\s+([0-9.]+)", text, re.M)
+    if not m or not rounds:
+        return None
+    return m.group(1), int(m.group(2)) / int(rounds.group(1)), float(m.group(4))
+
+
 # ---------------------------------------------------------------------------------------------- oracle baseline
 def _oracle_block_round(task):
     """One full round of the oracle on one block of all n workers (blocks are independent THC instances)."""
@@ -299,6 +314,16 @@ def main():
                      "algorithmic_bytes": fwd_alg_bytes, "launch_ms": fwd_ms,
                      "traffic": measured_traffic(w.name) if default_config else None},
     }
+    pk = profiled_kernel(w.name, "k_fwd_lo") if default_config else None
+    if pk is not None:
+        # The sweep's largest kernel by itself, from the tracked rocprofv3 summary (not measured in this run): the
+        # gradients (and error-feedback buffers) its launch reads, over its average duration.
+        name, per_round, avg_us = pk
+        lo_bytes = w.n * w.d * (in_bytes + (4 if w.ef else 0)) / per_round
+        result["roofline"]["largest_kernel"] = {"name": name, "launches_per_round": per_round, "avg_us": avg_us,
+                                                "algorithmic_bytes": lo_bytes,
+                                                "frac": lo_bytes / (avg_us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+                                                "source": f"profiles/all_kernels_{w.name}.txt"}
     if w.name == "c3_vgg16" and default_config:
         # Vector-ALU view of the same sweep: wave64 instructions it issues (rocprofv3 SQ_INSTS_VALU,
         # profiles/sq_counters_c3_vgg16.txt) against what 1024 SIMDs issue at one instruction per 4 cycles, 2.35 GHz

@@ -40,3 +40,9 @@ def test_counted_traffic_of_the_default_workload_is_read_from_the_tracked_profil
     # the forward sweep moves 12.5 bytes per worker-coordinate through the L2s (and 16 MiB of partial sums)
     assert 0.99 < t / (8 * 2 ** 28 * 12.5) < 1.02
     assert bench.measured_traffic("no_such_workload") is None
+
+
+def test_the_largest_kernel_of_the_default_workload_is_read_from_the_tracked_profile():
+    name, per_round, avg_us = bench.profiled_kernel("c3_vgg16", "k_fwd_lo")
+    assert name.startswith("k_fwd_lo<13") and per_round == 4 and 500 < avg_us < 1000
+    assert bench.profiled_kernel("no_such_workload", "k_fwd_lo") is None
